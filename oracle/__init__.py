@@ -1,0 +1,119 @@
+"""fp64 CPU oracle of the low-rank delta-rule recurrence (ParallelFlow, arXiv 2504.00492).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by ``__graft_entry__.smoke()`` and by the
+``cpu_baseline`` leg of ``bench.py``.  Nothing in the product package imports this, and this
+package imports nothing from the product package.
+
+* ``pf_oracle.c``      token-by-token recurrence (Section 1.1 recurrence/readout, Section 3.1
+                       discretised dynamics, delta mapping of the Remark in Section 3.1), plain C.
+* ``chunk_flow_ref.py`` numpy fp64 transcription of the chunk flow (Theorem 3.2, Proposition 3.3,
+                       Theorem 3.4); used by the tests only, to pin the recurrence from a second,
+                       independent direction.
+
+Parity status: every function here is pinned by tests/test_oracle_pins.py (closed forms,
+textbook special cases, library routines, brute force); nothing is "parity unpinned".
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "pf_oracle.c")
+_LIB = os.path.join(_HERE, "libpf_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile pf_oracle.c with gcc (no HIP, no ROCm headers).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(ctypes.c_double)
+        fp = ctypes.POINTER(ctypes.c_float)
+        lib.pf_oracle_flow_head.restype = ctypes.c_int
+        lib.pf_oracle_flow_head.argtypes = [dp, dp, dp, dp, dp, dp, dp] + [ctypes.c_int] * 4
+        lib.pf_oracle_delta_fwd.restype = ctypes.c_int
+        lib.pf_oracle_delta_fwd.argtypes = [fp, fp, fp, fp, fp, dp, dp] + [ctypes.c_int] * 6
+        lib.pf_oracle_max_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _dptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _fptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def max_threads() -> int:
+    return int(_load().pf_oracle_max_threads())
+
+
+def flow_head(A, Atil, Bm, Q, S0=None, want_O=True):
+    """General-driver recurrence for one head.
+
+    A, Bm: [L, R, dk]; Atil: [L, R, dv]; Q: [L, dk]; S0: [dv, dk] or None.
+    Returns (O [L, dv] or None, S_L [dv, dk]) in float64.
+    """
+    A = np.ascontiguousarray(A, dtype=np.float64)
+    Atil = np.ascontiguousarray(Atil, dtype=np.float64)
+    Bm = np.ascontiguousarray(Bm, dtype=np.float64)
+    Q = np.ascontiguousarray(Q, dtype=np.float64)
+    L, R, dk = A.shape
+    dv = Atil.shape[2]
+    assert Bm.shape == (L, R, dk) and Atil.shape == (L, R, dv) and Q.shape == (L, dk)
+    S0c = None if S0 is None else np.ascontiguousarray(S0, dtype=np.float64)
+    if S0c is not None:
+        assert S0c.shape == (dv, dk)
+    O = np.empty((L, dv), dtype=np.float64) if want_O else None
+    SL = np.empty((dv, dk), dtype=np.float64)
+    rc = _load().pf_oracle_flow_head(_dptr(A), _dptr(Atil), _dptr(Bm), _dptr(Q), _dptr(S0c),
+                                     _dptr(O), _dptr(SL), L, R, dk, dv)
+    if rc != 0:
+        raise MemoryError("pf_oracle_flow_head")
+    return O, SL
+
+
+def delta_fwd(Q, K, V, beta, S0=None, want_O=True, nthreads=0):
+    """Delta-rule recurrence over independent heads.
+
+    Q: [..., L, dk]; K: [..., L, R, dk]; V: [..., L, R, dv]; beta: [..., L, R];
+    S0: [..., dv, dk] or None.  Leading dims (e.g. B, H) are flattened.  Inputs are taken as
+    float32 (a bf16 workload passes its already-rounded values) and widened to float64.
+    Returns (O [..., L, dv] or None, S_L [..., dv, dk]) in float64.
+    """
+    K = np.ascontiguousarray(K, dtype=np.float32)
+    lead = K.shape[:-3]
+    L, R, dk = K.shape[-3:]
+    V = np.ascontiguousarray(V, dtype=np.float32)
+    dv = V.shape[-1]
+    Q = np.ascontiguousarray(Q, dtype=np.float32)
+    beta = np.ascontiguousarray(beta, dtype=np.float32)
+    assert V.shape == lead + (L, R, dv) and Q.shape == lead + (L, dk) and beta.shape == lead + (L, R)
+    N = int(np.prod(lead)) if lead else 1
+    S0c = None
+    if S0 is not None:
+        S0c = np.ascontiguousarray(S0, dtype=np.float32)
+        assert S0c.shape == lead + (dv, dk)
+    O = np.empty(lead + (L, dv), dtype=np.float64) if want_O else None
+    SL = np.empty(lead + (dv, dk), dtype=np.float64)
+    rc = _load().pf_oracle_delta_fwd(_fptr(Q), _fptr(K), _fptr(V), _fptr(beta), _fptr(S0c),
+                                     _dptr(O), _dptr(SL), N, L, R, dk, dv, int(nthreads))
+    if rc != 0:
+        raise MemoryError("pf_oracle_delta_fwd")
+    return O, SL
