@@ -1,0 +1,141 @@
+/*
+ * pf.h - C ABI of the MI355X (gfx950) chunked forward of the low-rank delta rule
+ *        (ParallelFlow, arXiv 2504.00492).
+ *
+ * The operation (one independent recurrence per (b, h)):
+ *
+ *     S_t = S_{t-1} (I - sum_j beta_{t,j} k_{t,j} k_{t,j}^T) + sum_j beta_{t,j} v_{t,j} k_{t,j}^T
+ *     o_t = S_t q_t                          t = 0 .. L-1,  j = 0 .. r-1,  S in R^{d_v x d_k}
+ *
+ * i.e. the discretised dynamics of Section 3.1 under the delta mapping of the Remark in
+ * Section 3.1 (A = beta k, Atil = -beta v, B = -k; rank r = one additive rank-r increment
+ * per token), with the "memory readout" of Section 1.1 on the updated state.  For r = 1 this
+ * is the DeltaNet update of Section 1.3.  It is computed chunk by chunk as the flow of the
+ * system (Section 3): per chunk the compact form W, U of Theorem 3.2, obtained by the block
+ * forward substitution of Proposition 3.3; the readout inside the chunk from the same W, U;
+ * and a state hand-over from chunk to chunk.
+ *
+ * Conventions common to every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never
+ *     allocates, frees or synchronises; work is enqueued on `stream` and returns at once.
+ *   - Tensors are dense, row-major, innermost dimension contiguous, base addresses 16-byte
+ *     aligned (PF_ERR_ALIGN otherwise).
+ *   - `dt` is the element type of Q, K, V, beta and O.  S0, S_L are always fp32.  All
+ *     accumulation is fp32; for PF_BF16 the MFMA operands are bf16.
+ *   - beta is used as given (any real value); keys are not normalised; q is not scaled.
+ *   - Errors are return codes; nothing is printed, thrown or aborted.  Every argument check
+ *     happens on the host before anything is launched, so a failing call has no effect.
+ *   - Calls that share a workspace (or outputs) must be ordered by the caller (same stream).
+ */
+#ifndef PF_H
+#define PF_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PF_OK = 0,
+    PF_ERR_NULL = 1,        /* a required pointer is NULL */
+    PF_ERR_SHAPE = 2,       /* a dimension is <= 0, or L is not a multiple of chunk where required */
+    PF_ERR_UNSUPPORTED = 3, /* no kernel instance for this (d_k, d_v, r, chunk, dt) */
+    PF_ERR_ALIGN = 4,       /* a base address is not 16-byte aligned */
+    PF_ERR_WORKSPACE = 5,   /* workspace is NULL or smaller than pf_delta_fwd_workspace_bytes() */
+    PF_ERR_LAUNCH = 6       /* the HIP runtime refused a launch */
+} pf_status;
+
+typedef enum { PF_F32 = 0, PF_BF16 = 1 } pf_dtype;
+
+/* A hipStream_t, passed as an opaque pointer so that this header needs no HIP header.
+ * NULL is the default stream. */
+typedef void *pf_stream;
+
+/* Library version: major * 10000 + minor * 100 + patch.  Host only. */
+int pf_version(void);
+
+/* Static, never-NULL description of a status code.  Host only. */
+const char *pf_status_str(pf_status s);
+
+/* Which kernel family would serve these dimensions.  Host only, no GPU needed.
+ *   0  unsupported (pf_delta_fwd would return PF_ERR_UNSUPPORTED)
+ *   1  generic path: one workgroup per (b, h), fp32 vector arithmetic, chunk state in LDS;
+ *      any d_k, d_v, r, chunk whose per-chunk working set fits 160 KiB of LDS; both dtypes;
+ *      L need not be a multiple of chunk (the tail is a shorter last chunk)
+ *   2  MFMA path (PF_BF16 only): d_k = d_v in {64, 128}, n = chunk * r in {64, 128, 256},
+ *      chunk in {64, 128}, L a multiple of chunk
+ */
+int pf_delta_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt);
+
+/* Bytes of device scratch pf_delta_fwd needs for these dimensions (0 for the generic path and
+ * for unsupported dimensions).  Host only. */
+size_t pf_delta_fwd_workspace_bytes(int B, int H, int L, int d_k, int d_v, int r, int chunk,
+                                    pf_dtype dt);
+
+/*
+ * Chunked forward of the rank-r delta rule (problem statement: Sections 1.1, 1.3, 3.1;
+ * method: Section 3 steps 1-3 and Theorem 3.2).
+ *
+ *   Q     [B, H, L, d_k]      dt     in
+ *   K     [B, H, L, r, d_k]   dt     in   (r keys per token = L*r "virtual tokens")
+ *   V     [B, H, L, r, d_v]   dt     in
+ *   beta  [B, H, L, r]        dt     in
+ *   S0    [B, H, d_v, d_k]    fp32   in   initial state; NULL means zeros
+ *   O     [B, H, L, d_v]      dt     out  o_t = S_t q_t (state AFTER token t)
+ *   S_L   [B, H, d_v, d_k]    fp32   out  final state; NULL means "do not write".
+ *                                         S_L == S0 (in-place state) is allowed.
+ *   workspace / workspace_bytes      device scratch of at least
+ *                                    pf_delta_fwd_workspace_bytes(...) bytes (may be NULL when
+ *                                    that is 0).  Contents are overwritten.
+ *   stream                           hipStream_t the kernels are enqueued on
+ *
+ * O and S_L must not overlap any input except S_L == S0.
+ * Returns PF_OK after enqueueing, else the first failed check (see pf_status).
+ * L == 0 is valid: the five sequence pointers may then be NULL, nothing is written to O and
+ * S_L receives S0 (or zeros).
+ */
+pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *beta,
+                       const float *S0, void *O, float *S_L,
+                       int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt,
+                       void *workspace, size_t workspace_bytes, pf_stream stream);
+
+/*
+ * Step 2 of Section 3 on its own ("parallel compute": the flow of every chunk, no dependence
+ * between chunks), MFMA path only (pf_delta_fwd_supported(...) == 2).  With n = chunk * r and
+ * NC = L / chunk, for every (b, h, c):
+ *
+ *   Cmat  = Id + M (.) diag(beta) K K^T,  M[(t,i),(s,j)] = 1 iff s < t     (Theorem 3.2 in delta
+ *           variables; Id - M (.) A B^T of the theorem)
+ *   Wneg  [B, H, NC, n, d_k]   bf16  out   -Cmat^{-1} (beta (.) K)   = -W of Theorem 3.2
+ *   UpT   [B, H, NC, d_v, n]   bf16  out   (Cmat^{-1} (beta (.) V))^T = -U^T of Theorem 3.2,
+ *                                          stored feature-major (transposed)
+ *   KT    [B, H, NC, d_k, n]   bf16  out   the chunk's keys, transposed
+ *   P     [B, H, NC, chunk, n] bf16  out   Mbar (.) Q K^T, Mbar[t,(s,j)] = 1 iff s <= t
+ *
+ * Inputs as in pf_delta_fwd.  All four outputs are required.
+ */
+pf_status pf_delta_chunk_flow(const void *Q, const void *K, const void *V, const void *beta,
+                              void *Wneg, void *UpT, void *KT, void *P,
+                              int B, int H, int L, int d_k, int d_v, int r, int chunk,
+                              pf_stream stream);
+
+/*
+ * Step 3 of Section 3 fused with the readout, MFMA path only: hands the state from chunk to
+ * chunk and reads out inside each chunk, from the arrays pf_delta_chunk_flow wrote:
+ *
+ *   U_eff = U' - W S_c^T          (U + W S_0^T of Theorem 3.2, up to the sign convention)
+ *   O_c   = Q S_c^T + P U_eff      (discrete flow of Section 3.1 truncated at each token)
+ *   S_c+1 = S_c + U_eff^T K        (S_1 of Theorem 3.2)
+ *
+ * Q, S0, O, S_L as in pf_delta_fwd (dt = PF_BF16).
+ */
+pf_status pf_delta_chunk_scan(const void *Q, const void *Wneg, const void *UpT, const void *KT,
+                              const void *P, const float *S0, void *O, float *S_L,
+                              int B, int H, int L, int d_k, int d_v, int r, int chunk,
+                              pf_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PF_H */

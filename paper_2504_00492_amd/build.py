@@ -1,0 +1,44 @@
+"""Builds the gfx950 shared library (libpf.so) in-tree with hipcc.
+
+`python -m paper_2504_00492_amd.build` or `build_library()`.  Cross-compiles without a GPU.
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libpf.so")
+SOURCES = ["pf_api.hip", "pf_generic.hip", "pf_flow.hip", "pf_scan.hip"]
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+# Packed-fp32 VALU forms are switched off for every kernel of this library.
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-value",
+         "-Wno-unknown-warning-option",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def _compile(src: str) -> str:
+    obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+    subprocess.run([HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj], check=True)
+    return obj
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile every source and link libpf.so.  Always recompiles."""
+    with ThreadPoolExecutor(max_workers=min(4, len(SOURCES))) as ex:
+        objs = list(ex.map(_compile, SOURCES))
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
+    if verbose:
+        print("built", LIB, file=sys.stderr)
+    return LIB
+
+
+def library_path() -> str:
+    return LIB
+
+
+if __name__ == "__main__":
+    build_library(verbose=True)

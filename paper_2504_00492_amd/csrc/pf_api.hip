@@ -1,0 +1,152 @@
+// C ABI of include/pf.h: argument checks on the host, then dispatch to the kernel launchers.
+#include "../../include/pf.h"
+#include "pf_internal.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Offsets (bytes) of the four per-chunk arrays inside the MFMA path's workspace.
+struct WorkspacePlan {
+    size_t oW, oU, oK, oP, total;
+};
+WorkspacePlan plan_workspace(int heads, int L, int d, int r, int chunk)
+{
+    const size_t n = (size_t)chunk * r;
+    const size_t tok = (size_t)heads * L;          // tokens over all heads
+    const size_t wk = tok * r * d * 2;             // Wneg, UpT, KT: bf16 [heads, L*r, d]
+    const size_t pb = tok * n * 2;                 // P: bf16 [heads, L, n]
+    WorkspacePlan p;
+    size_t o = 0;
+    p.oW = o; o = round_up(o + wk, kAlign);
+    p.oU = o; o = round_up(o + wk, kAlign);
+    p.oK = o; o = round_up(o + wk, kAlign);
+    p.oP = o; o = round_up(o + pb, kAlign);
+    p.total = o;
+    return p;
+}
+
+int family(int d_k, int d_v, int r, int chunk, pf_dtype dt)
+{
+    if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return 0;
+    if (dt != PF_F32 && dt != PF_BF16) return 0;
+    if (dt == PF_BF16 && d_k == d_v && (long long)chunk * r <= 4096 &&
+        pf::mfma_instance_exists(d_k, chunk * r, chunk))
+        return 2;
+    if ((long long)chunk * r > 65536 || d_k > 65536 || d_v > 65536) return 0;
+    if (pf::generic_lds_bytes(d_k, d_v, r, chunk) <= pf::kMaxLdsBytes) return 1;
+    return 0;
+}
+
+pf_status check_dims(int B, int H, int L, int d_k, int d_v, int r, int chunk)
+{
+    if (B <= 0 || H <= 0 || L < 0 || d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return PF_ERR_SHAPE;
+    if ((long long)B * H > 0x7fffffffLL) return PF_ERR_SHAPE;
+    return PF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pf_version(void) { return 100; }
+
+const char *pf_status_str(pf_status s)
+{
+    switch (s) {
+    case PF_OK: return "ok";
+    case PF_ERR_NULL: return "a required pointer is NULL";
+    case PF_ERR_SHAPE: return "bad dimension (non-positive, or L not a multiple of chunk on the MFMA path)";
+    case PF_ERR_UNSUPPORTED: return "no kernel instance for these dimensions and dtype";
+    case PF_ERR_ALIGN: return "a base address is not 16-byte aligned";
+    case PF_ERR_WORKSPACE: return "workspace is NULL or too small";
+    case PF_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+    }
+    return "unknown status";
+}
+
+int pf_delta_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt)
+{
+    return family(d_k, d_v, r, chunk, dt);
+}
+
+size_t pf_delta_fwd_workspace_bytes(int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt)
+{
+    if (check_dims(B, H, L, d_k, d_v, r, chunk) != PF_OK) return 0;
+    if (family(d_k, d_v, r, chunk, dt) != 2 || L % chunk != 0) return 0;
+    return plan_workspace(B * H, L, d_k, r, chunk).total;
+}
+
+pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
+                       void *O, float *S_L, int B, int H, int L, int d_k, int d_v, int r, int chunk,
+                       pf_dtype dt, void *workspace, size_t workspace_bytes, pf_stream stream)
+{
+    if (L != 0 && (!Q || !K || !V || !beta || !O)) return PF_ERR_NULL;
+    pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
+    if (st != PF_OK) return st;
+    int fam = family(d_k, d_v, r, chunk, dt);
+    // The MFMA path needs whole chunks; a ragged L goes to the generic path when that fits.
+    if (fam == 2 && L % chunk != 0)
+        fam = (pf::generic_lds_bytes(d_k, d_v, r, chunk) <= pf::kMaxLdsBytes) ? 1 : -1;
+    if (fam == -1) return PF_ERR_SHAPE;
+    if (fam == 0) return PF_ERR_UNSUPPORTED;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(beta) || !aligned16(O) ||
+        !aligned16(S0) || !aligned16(S_L))
+        return PF_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int heads = B * H;
+    if (fam == 1 || L == 0) {
+        hipError_t e = pf::launch_generic(Q, K, V, beta, S0, O, S_L, heads, L, d_k, d_v, r, chunk,
+                                          dt == PF_BF16, s);
+        return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+    }
+    const WorkspacePlan wp = plan_workspace(heads, L, d_k, r, chunk);
+    if (!workspace || workspace_bytes < wp.total) return PF_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return PF_ERR_ALIGN;
+    char *ws = static_cast<char *>(workspace);
+    hipError_t e = pf::launch_chunk_flow(Q, K, V, beta, ws + wp.oW, ws + wp.oU, ws + wp.oK, ws + wp.oP,
+                                         heads, L, d_k, r, chunk, s);
+    if (e != hipSuccess) return PF_ERR_LAUNCH;
+    e = pf::launch_chunk_scan(Q, ws + wp.oW, ws + wp.oU, ws + wp.oK, ws + wp.oP, S0, O, S_L, heads, L,
+                              d_k, r, chunk, s);
+    return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+}
+
+pf_status pf_delta_chunk_flow(const void *Q, const void *K, const void *V, const void *beta, void *Wneg,
+                              void *UpT, void *KT, void *P, int B, int H, int L, int d_k, int d_v, int r,
+                              int chunk, pf_stream stream)
+{
+    if (!Q || !K || !V || !beta || !Wneg || !UpT || !KT || !P) return PF_ERR_NULL;
+    pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
+    if (st != PF_OK) return st;
+    if (family(d_k, d_v, r, chunk, PF_BF16) != 2) return PF_ERR_UNSUPPORTED;
+    if (L % chunk != 0) return PF_ERR_SHAPE;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(beta) || !aligned16(Wneg) ||
+        !aligned16(UpT) || !aligned16(KT) || !aligned16(P))
+        return PF_ERR_ALIGN;
+    if (L == 0) return PF_OK;
+    hipError_t e = pf::launch_chunk_flow(Q, K, V, beta, Wneg, UpT, KT, P, B * H, L, d_k, r, chunk,
+                                         static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+}
+
+pf_status pf_delta_chunk_scan(const void *Q, const void *Wneg, const void *UpT, const void *KT,
+                              const void *P, const float *S0, void *O, float *S_L, int B, int H, int L,
+                              int d_k, int d_v, int r, int chunk, pf_stream stream)
+{
+    if (!Q || !Wneg || !UpT || !KT || !P || !O) return PF_ERR_NULL;
+    pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
+    if (st != PF_OK) return st;
+    if (family(d_k, d_v, r, chunk, PF_BF16) != 2) return PF_ERR_UNSUPPORTED;
+    if (L % chunk != 0) return PF_ERR_SHAPE;
+    if (!aligned16(Q) || !aligned16(Wneg) || !aligned16(UpT) || !aligned16(KT) || !aligned16(P) ||
+        !aligned16(S0) || !aligned16(O) || !aligned16(S_L))
+        return PF_ERR_ALIGN;
+    hipError_t e = pf::launch_chunk_scan(Q, Wneg, UpT, KT, P, S0, O, S_L, B * H, L, d_k, r, chunk,
+                                         static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,27 @@
+// Host-side launchers behind the C ABI of include/pf.h.  Each returns the HIP status of its
+// launch; none of them allocates, frees or synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace pf {
+
+constexpr size_t kMaxLdsBytes = 160 * 1024;  // LDS per workgroup on gfx950
+
+// ---- generic path (pf_generic.hip)
+size_t generic_lds_bytes(int dk, int dv, int r, int chunk);
+hipError_t launch_generic(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
+                          void *O, float *SL, int heads, int L, int dk, int dv, int r, int chunk,
+                          bool is_bf16, hipStream_t stream);
+
+// ---- MFMA path (pf_flow.hip, pf_scan.hip); d = d_k = d_v, n = chunk * r
+bool mfma_instance_exists(int d, int n, int chunk);
+hipError_t launch_chunk_flow(const void *Q, const void *K, const void *V, const void *beta,
+                             void *Wneg, void *UpT, void *KT, void *P,
+                             int heads, int L, int d, int r, int chunk, hipStream_t stream);
+hipError_t launch_chunk_scan(const void *Q, const void *Wneg, const void *UpT, const void *KT,
+                             const void *P, const float *S0, void *O, float *SL,
+                             int heads, int L, int d, int r, int chunk, hipStream_t stream);
+
+}  // namespace pf

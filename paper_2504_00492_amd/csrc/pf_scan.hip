@@ -1,0 +1,204 @@
+// State-passing scan fused with the intra-chunk readout: step 3 of Section 3 of ParallelFlow
+// (arXiv 2504.00492) as a sequential hand-over of S from chunk to chunk.
+//
+// Rows of S evolve independently (the recurrence of Section 3.1 multiplies S from the right),
+// so a workgroup owns TV rows of S (a tile of d_v) of one (b, h) and walks the chunks:
+//     U_eff = U' - W S_c^T            n x TV      (U + W S_0^T of Theorem 3.2, sign folded)
+//     O_c   = Q S_c^T + P U_eff       chunk x TV  (discrete flow of Section 3.1 cut at each t)
+//     S_c+1 = S_c + U_eff^T K         TV x d      (S_1 of Theorem 3.2)
+// with W, U', K^T, P as written by the chunk-flow kernel.
+//
+// Data movement.  S^T lives in fp32 accumulators (wave w owns d_k rows [w d/4, (w+1) d/4));
+// a bf16 copy in LDS ([d_v][d_k], double buffered) feeds the MFMA operands of the next chunk.
+// U_eff goes through LDS once ([d_v][n]: accumulator tiles are 4 consecutive tokens of one
+// feature, i.e. 8-byte writes).  W, K^T, Q and P are each used by exactly one wave, so they
+// are loaded straight from global memory into MFMA operand registers.  O is computed
+// transposed (rows = d_v) so that a lane ends up with 4 consecutive features of one token.
+#include "pf_internal.h"
+#include "pf_common.cuh"
+
+namespace pf {
+
+template <int D, int N, int TV>
+struct ScanLds {
+    static constexpr int SP = D + 8;   // pitch of a row of the bf16 state copy
+    static constexpr int UP = N + 8;   // pitch of a row of U_eff^T
+    static constexpr size_t oSb = 0;
+    static constexpr size_t oUe = oSb + (size_t)2 * TV * SP * 2;
+    static constexpr size_t total = oUe + (size_t)TV * UP * 2;
+};
+
+template <int D, int N, int C, int TV>
+__global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Q, const bf16 *__restrict__ Wneg,
+                                                   const bf16 *__restrict__ UpT, const bf16 *__restrict__ KT,
+                                                   const bf16 *__restrict__ P, const float *S0,
+                                                   bf16 *__restrict__ O, float *SL, int nchains, int NC)
+{
+    using Ld = ScanLds<D, N, TV>;
+    constexpr int R = N / C;
+    constexpr int NKS = D / 32;        // k-steps over d
+    constexpr int NNT = TV / 16;       // 16-wide tiles over this workgroup's d_v rows
+    constexpr int MPW = D / 64;        // d_k tiles (16 rows of S^T) owned by one wave
+    constexpr int SP = Ld::SP, UP = Ld::UP;
+    static_assert(D % 64 == 0 && TV % 16 == 0 && N % 32 == 0 && C % 16 == 0, "tile shapes");
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16 *Sb = reinterpret_cast<bf16 *>(smem + Ld::oSb);
+    bf16 *Ue = reinterpret_cast<bf16 *>(smem + Ld::oUe);
+
+    const int tid = threadIdx.x;
+    const int w = tid >> 6, lane = tid & 63;
+    const int r16 = lane & 15, g = lane >> 4;
+
+    // Workgroups of one (b, h) are nchains apart in blockIdx, hence on the same XCD (block ids
+    // go round-robin over the 8 XCDs) and share that XCD's L2 for the operands they all read.
+    const int tile = blockIdx.x / nchains;
+    const size_t chain = blockIdx.x % nchains;
+    const int dv0 = tile * TV;
+
+    // ---- initial state: fp32 accumulators + bf16 copy
+    f32x4 sacc[MPW][NNT];
+#pragma unroll
+    for (int a = 0; a < MPW; ++a)
+#pragma unroll
+        for (int nt = 0; nt < NNT; ++nt) {
+            const int mt = w * MPW + a;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (S0) v = *reinterpret_cast<const f32x4 *>(S0 + chain * (size_t)D * D +
+                                                         (size_t)(dv0 + 16 * nt + r16) * D + 16 * mt + 4 * g);
+            sacc[a][nt] = v;
+            st4(&Sb[(16 * nt + r16) * SP + 16 * mt + 4 * g], cvt4(v));
+        }
+    __syncthreads();
+
+    for (int ch = 0; ch < NC; ++ch) {
+        const int cur = ch & 1;
+        const size_t cid = chain * (size_t)NC + ch;
+        const bf16 *Wc = Wneg + cid * (size_t)N * D;
+        const bf16 *Uc = UpT + cid * (size_t)N * D;
+        const bf16 *Kc = KT + cid * (size_t)N * D;
+        const bf16 *Pc = P + cid * (size_t)C * N;
+        const bf16 *Qc = Q + cid * (size_t)C * D;
+        bf16 *Oc = O + cid * (size_t)C * D;
+        const bf16 *Scur = Sb + cur * TV * SP;
+
+        // ---- (1) U_eff = U' + Wneg S^T : rows (virtual tokens) dealt to the waves
+        {
+            bf16x8 bS[NNT][NKS];
+#pragma unroll
+            for (int nt = 0; nt < NNT; ++nt)
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks) bS[nt][ks] = ld8(&Scur[(16 * nt + r16) * SP + 32 * ks + 8 * g]);
+            for (int mt = w; mt < N / 16; mt += 4) {
+                f32x4 acc[NNT];
+                bf16x8 a[NKS];
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks) a[ks] = ld8(Wc + (size_t)(16 * mt + r16) * D + 32 * ks + 8 * g);
+#pragma unroll
+                for (int nt = 0; nt < NNT; ++nt)
+                    acc[nt] = __builtin_convertvector(ld4(Uc + (size_t)(dv0 + 16 * nt + r16) * N + 16 * mt + 4 * g), f32x4);
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+                    for (int nt = 0; nt < NNT; ++nt) acc[nt] = mfma16(a[ks], bS[nt][ks], acc[nt]);
+#pragma unroll
+                for (int nt = 0; nt < NNT; ++nt) st4(&Ue[(16 * nt + r16) * UP + 16 * mt + 4 * g], cvt4(acc[nt]));
+            }
+        }
+        __syncthreads();
+
+        // ---- (2) O^T = S Q^T + U_eff^T P^T : token tiles dealt to the waves
+        for (int tt = w; tt < C / 16; tt += 4) {
+            f32x4 oacc[NNT];
+#pragma unroll
+            for (int md = 0; md < NNT; ++md) oacc[md] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                bf16x8 b = ld8(Qc + (size_t)(16 * tt + r16) * D + 32 * ks + 8 * g);
+#pragma unroll
+                for (int md = 0; md < NNT; ++md)
+                    oacc[md] = mfma16(ld8(&Scur[(16 * md + r16) * SP + 32 * ks + 8 * g]), b, oacc[md]);
+            }
+            // causal: tokens <= 16 tt + 15 means virtual tokens < R (16 tt + 16)
+            const int ksteps = (R * (16 * tt + 16) + 31) / 32;
+            for (int ks = 0; ks < ksteps; ++ks) {
+                bf16x8 b = ld8(Pc + (size_t)(16 * tt + r16) * N + 32 * ks + 8 * g);
+#pragma unroll
+                for (int md = 0; md < NNT; ++md)
+                    oacc[md] = mfma16(ld8(&Ue[(16 * md + r16) * UP + 32 * ks + 8 * g]), b, oacc[md]);
+            }
+#pragma unroll
+            for (int md = 0; md < NNT; ++md)
+                st4(Oc + (size_t)(16 * tt + r16) * D + dv0 + 16 * md + 4 * g, cvt4(oacc[md]));
+        }
+
+        // ---- (3) S^T += K^T U_eff : this wave's d_k rows
+        for (int ks = 0; ks < N / 32; ++ks) {
+            bf16x8 b[NNT];
+#pragma unroll
+            for (int nt = 0; nt < NNT; ++nt) b[nt] = ld8(&Ue[(16 * nt + r16) * UP + 32 * ks + 8 * g]);
+#pragma unroll
+            for (int a = 0; a < MPW; ++a) {
+                bf16x8 ak = ld8(Kc + (size_t)(16 * (w * MPW + a) + r16) * N + 32 * ks + 8 * g);
+#pragma unroll
+                for (int nt = 0; nt < NNT; ++nt) sacc[a][nt] = mfma16(ak, b[nt], sacc[a][nt]);
+            }
+        }
+        bf16 *Snext = Sb + (cur ^ 1) * TV * SP;
+#pragma unroll
+        for (int a = 0; a < MPW; ++a)
+#pragma unroll
+            for (int nt = 0; nt < NNT; ++nt)
+                st4(&Snext[(16 * nt + r16) * SP + 16 * (w * MPW + a) + 4 * g], cvt4(sacc[a][nt]));
+        __syncthreads();
+    }
+
+    if (SL) {
+#pragma unroll
+        for (int a = 0; a < MPW; ++a)
+#pragma unroll
+            for (int nt = 0; nt < NNT; ++nt)
+                *reinterpret_cast<f32x4 *>(SL + chain * (size_t)D * D + (size_t)(dv0 + 16 * nt + r16) * D +
+                                           16 * (w * MPW + a) + 4 * g) = sacc[a][nt];
+    }
+}
+
+// ---------------------------------------------------------------------------- host side
+#define PF_SCAN_INSTANCES(X) \
+    X(64, 64, 64) X(64, 128, 64) X(64, 128, 128) X(64, 256, 64) X(64, 256, 128) \
+    X(128, 64, 64) X(128, 128, 64) X(128, 128, 128) X(128, 256, 64) X(128, 256, 128)
+
+template <int D, int N, int C, int TV>
+static hipError_t launch_scan_instance(const void *Q, const void *Wneg, const void *UpT, const void *KT,
+                                       const void *P, const float *S0, void *O, float *SL, int heads,
+                                       int NC, hipStream_t stream)
+{
+    auto kern = scan_kernel<D, N, C, TV>;
+    constexpr size_t lds = ScanLds<D, N, TV>::total;
+    static_assert(lds <= 64 * 1024, "scan kernel is meant to leave room for several workgroups per CU");
+    const unsigned grid = (unsigned)heads * (D / TV);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, (const bf16 *)Q, (const bf16 *)Wneg,
+                       (const bf16 *)UpT, (const bf16 *)KT, (const bf16 *)P, S0, (bf16 *)O, SL, heads, NC);
+    return hipGetLastError();
+}
+
+hipError_t launch_chunk_scan(const void *Q, const void *Wneg, const void *UpT, const void *KT,
+                             const void *P, const float *S0, void *O, float *SL, int heads, int L, int d,
+                             int r, int chunk, hipStream_t stream)
+{
+    const int NC = L / chunk;
+    const int n = chunk * r;
+    if ((long long)heads * (d / 16) > 0x7fffffffLL) return hipErrorInvalidValue;
+    // d_v tile per workgroup: 32 rows when that already gives at least one workgroup per CU,
+    // else 16 rows (twice the workgroups, half the MFMA work per operand byte).
+    const bool wide = (long long)heads * (d / 32) >= 256;
+#define X(DD, NN, CC)                                                                                   \
+    if (d == DD && n == NN && chunk == CC)                                                               \
+        return wide ? launch_scan_instance<DD, NN, CC, 32>(Q, Wneg, UpT, KT, P, S0, O, SL, heads, NC, stream) \
+                    : launch_scan_instance<DD, NN, CC, 16>(Q, Wneg, UpT, KT, P, S0, O, SL, heads, NC, stream);
+    PF_SCAN_INSTANCES(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+}  // namespace pf

@@ -1,0 +1,127 @@
+"""Host-side checks of the C ABI: the library loads, exports what include/pf.h declares, and
+every argument check returns its code before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2504_00492_amd", "libpf.so")
+
+
+@pytest.fixture(scope="module")
+def pf():
+    if not os.path.exists(LIB):
+        from paper_2504_00492_amd import build
+        build.build_library()
+    from paper_2504_00492_amd import binding
+    return binding
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "pf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pf_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(pf):
+    names = _declared_functions()
+    assert "pf_delta_fwd" in names and len(names) >= 7
+    lib = ctypes.CDLL(LIB)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(pf.EXPORTS) == names
+
+
+def test_version_and_status_strings(pf):
+    assert pf.pf_version() >= 100
+    seen = {pf.pf_status_str(s) for s in range(7)}
+    assert len(seen) == 7 and all(seen)
+    assert pf.pf_status_str(99) == "unknown status"
+
+
+def test_supported_families(pf):
+    BF, F32 = pf.PF_BF16, pf.PF_F32
+    assert pf.pf_delta_fwd_supported(16, 16, 1, 16, F32) == 1          # config 0
+    assert pf.pf_delta_fwd_supported(64, 64, 1, 64, BF) == 2           # config 1
+    assert pf.pf_delta_fwd_supported(128, 128, 2, 64, BF) == 2         # config 2
+    assert pf.pf_delta_fwd_supported(128, 128, 4, 64, BF) == 2         # config 3, chunk 64
+    assert pf.pf_delta_fwd_supported(128, 128, 2, 128, BF) == 2        # config 4
+    assert pf.pf_delta_fwd_supported(128, 128, 2, 64, F32) == 0        # fp32 at that size: no LDS room
+    assert pf.pf_delta_fwd_supported(20, 12, 3, 8, BF) == 1            # odd shape -> generic
+    assert pf.pf_delta_fwd_supported(0, 16, 1, 16, F32) == 0
+    assert pf.pf_delta_fwd_supported(16, 16, 1, 16, 7) == 0
+
+
+def test_workspace_bytes(pf):
+    BF = pf.PF_BF16
+    assert pf.pf_delta_fwd_workspace_bytes(1, 1, 64, 16, 16, 1, 16, pf.PF_F32) == 0
+    b = pf.pf_delta_fwd_workspace_bytes(4, 16, 4096, 128, 128, 2, 64, BF)
+    tok = 4 * 16 * 4096
+    assert b >= tok * 2 * 128 * 2 * 3 + tok * 128 * 2 and b % 256 == 0
+    assert pf.pf_delta_fwd_workspace_bytes(4, 16, 4097, 128, 128, 2, 64, BF) == 0   # ragged -> generic or error
+    assert pf.pf_delta_fwd_workspace_bytes(0, 16, 4096, 128, 128, 2, 64, BF) == 0
+
+
+def test_argument_checks_return_before_launch(pf):
+    """Fake (never dereferenced) addresses: each call must fail its check on the host."""
+    A = 0x10000  # 16-byte aligned fake device address
+    BF = pf.PF_BF16
+    dims = dict(B=1, H=1, L=128, d_k=128, d_v=128, r=2, chunk=64)
+
+    def call(Q=A, K=A, V=A, beta=A, S0=A, O=A, SL=A, ws=A, wb=1 << 40, dt=BF, **kw):
+        d = dict(dims, **kw)
+        return pf.pf_delta_fwd(Q, K, V, beta, S0, O, SL, d["B"], d["H"], d["L"], d["d_k"], d["d_v"], d["r"],
+                               d["chunk"], dt, ws, wb, 0)
+
+    assert call(Q=None) == pf.PF_ERR_NULL
+    assert call(K=None) == pf.PF_ERR_NULL
+    assert call(V=None) == pf.PF_ERR_NULL
+    assert call(beta=None) == pf.PF_ERR_NULL
+    assert call(O=None) == pf.PF_ERR_NULL
+    assert call(B=0) == pf.PF_ERR_SHAPE
+    assert call(L=-1) == pf.PF_ERR_SHAPE
+    assert call(r=0) == pf.PF_ERR_SHAPE
+    assert call(chunk=0) == pf.PF_ERR_SHAPE
+    assert call(L=100) == pf.PF_ERR_SHAPE              # MFMA shape, ragged L, too big for the generic path
+    assert call(dt=5) == pf.PF_ERR_UNSUPPORTED
+    assert call(dt=pf.PF_F32) == pf.PF_ERR_UNSUPPORTED  # fp32 with d = 128, n = 128 does not fit LDS
+    assert call(Q=A + 2) == pf.PF_ERR_ALIGN
+    assert call(SL=A + 4) == pf.PF_ERR_ALIGN
+    assert call(ws=None) == pf.PF_ERR_WORKSPACE
+    assert call(wb=16) == pf.PF_ERR_WORKSPACE
+    assert call(ws=A + 8) == pf.PF_ERR_ALIGN
+
+    flow = pf.pf_delta_chunk_flow
+    assert flow(A, A, A, A, None, A, A, A, 1, 1, 128, 128, 128, 2, 64, 0) == pf.PF_ERR_NULL
+    assert flow(A, A, A, A, A, A, A, A, 1, 1, 100, 128, 128, 2, 64, 0) == pf.PF_ERR_SHAPE
+    assert flow(A, A, A, A, A, A, A, A, 1, 1, 128, 20, 20, 2, 64, 0) == pf.PF_ERR_UNSUPPORTED
+    assert flow(A, A, A, A, A, A, A + 2, A, 1, 1, 128, 128, 128, 2, 64, 0) == pf.PF_ERR_ALIGN
+    scan = pf.pf_delta_chunk_scan
+    assert scan(A, A, A, A, A, A, None, A, 1, 1, 128, 128, 128, 2, 64, 0) == pf.PF_ERR_NULL
+    assert scan(A, A, A, A, A, A, A, A, 1, 1, 128, 128, 64, 2, 64, 0) == pf.PF_ERR_UNSUPPORTED
+    assert scan(A, A, A, A, A, A, A, A + 4, 1, 1, 128, 128, 128, 2, 64, 0) == pf.PF_ERR_ALIGN
+
+
+def test_inputs_are_seeded_and_bf16_exact():
+    import numpy as np
+    from paper_2504_00492_amd import synth
+    w = synth.WORKLOADS["cfg1"].with_(B=1, H=2, L=128)
+    a, b = synth.make_inputs(w), synth.make_inputs(w)
+    for k in ("Q", "K", "V", "beta"):
+        assert np.array_equal(a[k], b[k])
+        assert np.array_equal(synth.round_to_bf16(a[k]), a[k])          # already bf16 values
+        assert np.array_equal(synth.bf16_bits_to_f32(synth.bf16_bits(a[k])), a[k])
+    assert a["S0"] is None
+    h1 = synth.head_inputs(w, 1)
+    assert np.array_equal(h1[0], a["Q"][1])
+    # unit keys up to bf16 rounding; beta in (0, 1)
+    assert np.allclose(np.linalg.norm(a["K"], axis=-1), 1.0, atol=2e-2)
+    assert a["beta"].min() > 0 and a["beta"].max() < 1
+    w4 = synth.WORKLOADS["cfg4"].with_(L=4096)
+    q, k, v, beta, s0 = synth.head_inputs(w4, 0)
+    frac = np.mean(np.all(beta >= 1.5, axis=-1))
+    assert 0.05 < frac < 0.15 and beta.max() <= 2.0
+    w3 = synth.WORKLOADS["cfg3a"].with_(L=64)
+    assert abs(float(np.std(synth.head_inputs(w3, 0)[4])) - 0.1) < 0.01

@@ -1,0 +1,169 @@
+"""Parity of the HIP path (through the C ABI) with the fp64 oracle, element by element, on
+seeded inputs.  Bars: rel. L2 <= 1e-4 for fp32 inputs, <= 2e-2 for bf16 inputs (fp32
+accumulation), on both O and S_L; the recurrence has a unique result, so nothing else is
+"also correct"."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2504_00492_amd import synth
+from gpu_util import rel_l2, to_device, run_gpu, flat_heads
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def pf():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2504_00492_amd import binding
+    return binding
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _check(pf, oracle, w, expect_family=None, heads=None):
+    fam = pf.pf_delta_fwd_supported(w.d_k, w.d_v, w.r, w.chunk, pf.PF_BF16 if w.dtype == "bf16" else pf.PF_F32)
+    if expect_family is not None and w.L % w.chunk == 0:
+        assert fam == expect_family, (fam, expect_family)
+    _say(f"[case] {w.name} dtype={w.dtype} B={w.B} H={w.H} L={w.L} d=({w.d_k},{w.d_v}) r={w.r} C={w.chunk} family={fam}")
+    inp = synth.make_inputs(w)
+    dev = to_device(w, inp)
+    O, SL = run_gpu(pf, w, dev)
+    Oref, SLref = oracle.delta_fwd(inp["Q"], inp["K"], inp["V"], inp["beta"], inp["S0"])
+    eO, eS = rel_l2(flat_heads(O), Oref), rel_l2(flat_heads(SL), SLref)
+    worst = max(rel_l2(flat_heads(O)[h], Oref[h]) for h in range(w.heads))
+    _say(f"        relL2(O)={eO:.3e} relL2(S_L)={eS:.3e} worst head O={worst:.3e} |S_L|={np.linalg.norm(SLref):.3f}")
+    assert np.isfinite(O).all() and np.isfinite(SL).all()
+    assert eO <= TOL[w.dtype] and eS <= TOL[w.dtype]
+    return O, SL, Oref, SLref
+
+
+# ------------------------------------------------------------------ generic path (fp32 + odd shapes)
+def test_config0_fp32(pf, oracle):
+    _check(pf, oracle, synth.WORKLOADS["cfg0"], expect_family=1)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(B=2, H=3, L=40, d_k=12, d_v=20, r=2, chunk=8, s0_std=0.5),      # d_k != d_v, several tiles
+    dict(B=1, H=2, L=37, d_k=16, d_v=16, r=3, chunk=8, s0_std=0.3),      # ragged tail (37 = 4*8 + 5), r = 3
+    dict(B=1, H=1, L=5, d_k=8, d_v=8, r=1, chunk=16),                    # L < chunk
+    dict(B=1, H=2, L=16, d_k=32, d_v=24, r=4, chunk=1),                  # chunk = 1 is the recurrence itself
+    dict(B=1, H=1, L=64, d_k=64, d_v=64, r=1, chunk=32, reflect_frac=0.3),
+])
+def test_generic_fp32_shapes(pf, oracle, kw):
+    w = synth.Workload("gen", "f32", seed=11, **{"s0_std": 0.0, "reflect_frac": 0.0, **kw})
+    _check(pf, oracle, w, expect_family=1)
+
+
+def test_generic_bf16_odd_shape(pf, oracle):
+    w = synth.Workload("gen16", "bf16", 2, 2, 48, 24, 40, 2, 8, seed=12, s0_std=0.2)
+    _check(pf, oracle, w, expect_family=1)
+
+
+def test_empty_sequence_returns_initial_state(pf):
+    import torch
+    dev = torch.device("cuda:0")
+    S0 = torch.randn(1, 2, 16, 16, device=dev)
+    z = lambda *s: torch.zeros(s, device=dev)
+    O, SL = pf.delta_fwd(z(1, 2, 0, 16), z(1, 2, 0, 1, 16), z(1, 2, 0, 1, 16), z(1, 2, 0, 1), S0, chunk=16)
+    torch.cuda.synchronize()
+    assert O.shape == (1, 2, 0, 16) and torch.equal(SL, S0)
+
+
+# ------------------------------------------------------------------ chunk flow (Theorem 3.2) on its own
+@pytest.mark.parametrize("d,r,C", [(64, 1, 64), (128, 2, 64), (128, 4, 64), (128, 2, 128), (128, 1, 128), (64, 4, 64)])
+def test_chunk_flow_matches_theorem(pf, oracle, d, r, C):
+    """W, U', K^T and P of every chunk against the numpy statement of Theorem 3.2."""
+    import torch
+    from oracle import chunk_flow_ref as cf
+    w = synth.Workload("flow", "bf16", 1, 2, 2 * C, d, d, r, C, seed=21, reflect_frac=0.1)
+    _say(f"[case] chunk flow d={d} r={r} C={C}")
+    inp = synth.make_inputs(w)
+    dev = to_device(w, inp)
+    n, NC = C * r, w.L // C
+    mk = lambda *s: torch.empty(s, dtype=torch.bfloat16, device="cuda:0")
+    Wn, UpT, KT, P = mk(1, 2, NC, n, d), mk(1, 2, NC, d, n), mk(1, 2, NC, d, n), mk(1, 2, NC, C, n)
+    st = pf.pf_delta_chunk_flow(dev["Q"], dev["K"], dev["V"], dev["beta"], Wn, UpT, KT, P, 1, 2, w.L, d, d, r, C)
+    assert st == pf.PF_OK
+    torch.cuda.synchronize()
+    Wn, UpT, KT, P = (t.float().cpu().numpy() for t in (Wn, UpT, KT, P))
+    for h in range(2):
+        for c in range(NC):
+            sl = slice(c * C, (c + 1) * C)
+            A, At, Bm = cf.delta_drivers(inp["K"][h, sl], inp["V"][h, sl], inp["beta"][h, sl])
+            Wr, Ur = cf.chunk_flow(A, At, Bm)                     # paper's W and U (= -U')
+            Kf = inp["K"][h, sl].reshape(n, d).astype(np.float64)
+            Pr = cf.inclusive_time_mask(C, r) * (inp["Q"][h, sl].astype(np.float64) @ Kf.T)
+            assert rel_l2(Wn[0, h, c], -Wr) < 1e-2
+            assert rel_l2(UpT[0, h, c].T, -Ur) < 1e-2
+            assert np.array_equal(KT[0, h, c].T, inp["K"][h, sl].reshape(n, d))
+            assert rel_l2(P[0, h, c], Pr) < 5e-3
+            assert np.all(P[0, h, c][cf.inclusive_time_mask(C, r) == 0] == 0)
+
+
+# ------------------------------------------------------------------ MFMA path, sizes the oracle does in seconds
+@pytest.mark.parametrize("name,kw", [
+    ("cfg1", dict(B=2, H=4, L=512)),                 # r=1 d=64 C=64, 8 chunks
+    ("cfg2", dict(B=1, H=8, L=512)),                 # r=2 d=128 C=64
+    ("cfg3a", dict(B=1, H=4, L=256)),                # r=4 C=64, nonzero S0
+    ("cfg4", dict(B=1, H=4, L=1024)),                # r=2 C=128, near-reflection betas
+    ("cfg2", dict(B=4, H=16, L=128)),                # 64 heads -> 32-row d_v tiles (other scan instance)
+])
+def test_mfma_path_reduced_sizes(pf, oracle, name, kw):
+    w = synth.WORKLOADS[name].with_(**kw)
+    _check(pf, oracle, w, expect_family=2)
+
+
+@pytest.mark.parametrize("d,r,C", [(64, 2, 64), (64, 4, 64), (64, 2, 128), (128, 1, 64), (128, 1, 128), (64, 1, 64)])
+def test_mfma_other_instances(pf, oracle, d, r, C):
+    w = synth.Workload("inst", "bf16", 1, 3, 3 * C, d, d, r, C, seed=31, s0_std=0.1, reflect_frac=0.05)
+    _check(pf, oracle, w, expect_family=2)
+
+
+def test_mfma_single_chunk_and_beta_zero(pf, oracle):
+    import torch
+    w = synth.WORKLOADS["cfg2"].with_(B=1, H=2, L=64, s0_std=0.2)
+    _check(pf, oracle, w, expect_family=2)
+    # beta = 0: state must come back bit-identical, O = Q S0^T
+    inp = synth.make_inputs(w)
+    inp["beta"][:] = 0.0
+    dev = to_device(w, inp)
+    O, SL = run_gpu(pf, w, dev)
+    assert np.array_equal(flat_heads(SL), inp["S0"])
+    Oref = np.einsum("nld,nvd->nlv", inp["Q"].astype(np.float64), inp["S0"].astype(np.float64))
+    assert rel_l2(flat_heads(O), Oref) < 1e-2
+
+
+def test_mfma_in_place_state_split_sequence_and_determinism(pf, oracle):
+    """S_L may alias S0; one call over [0, L) equals two calls chained through the state
+    (Proposition 2.1); reruns are bit-identical (no atomics, fixed reduction order)."""
+    import torch
+    w = synth.WORKLOADS["cfg4"].with_(B=1, H=2, L=512, s0_std=0.1)
+    inp = synth.make_inputs(w)
+    dev = to_device(w, inp)
+    B, H, L, r, d = 1, 2, w.L, w.r, w.d_k
+    need = pf.pf_delta_fwd_workspace_bytes(B, H, L, d, d, r, w.chunk, pf.PF_BF16)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    O1, S1 = pf.delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], chunk=w.chunk, workspace=ws)
+    O2, S2 = pf.delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], chunk=w.chunk, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2) and torch.equal(S1, S2)
+    # two halves, state updated in place
+    half = L // 2
+    S = dev["S0"].clone()
+    Oa = torch.empty(B, H, half, d, dtype=torch.bfloat16, device="cuda:0")
+    Ob = torch.empty_like(Oa)
+    sl = lambda t, a, b: t[:, :, a:b].contiguous()
+    for (a, b, Oh) in ((0, half, Oa), (half, L, Ob)):
+        st = pf.pf_delta_fwd(sl(dev["Q"], a, b), sl(dev["K"], a, b), sl(dev["V"], a, b), sl(dev["beta"], a, b),
+                             S, Oh, S, B, H, half, d, d, r, w.chunk, pf.PF_BF16, ws, need)
+        assert st == pf.PF_OK
+    torch.cuda.synchronize()
+    assert torch.equal(torch.cat([Oa, Ob], dim=2), O1) and torch.equal(S, S1)
