@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the chunked rank-r delta-rule forward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2]
+
+One "step" is one pass of the whole hot path (chunk flow + state scan with fused readout, i.e.
+one pf_delta_fwd call) over one batch of seeded synthetic input that is already resident in
+HBM.  Prints ONE JSON line: tokens/s for the whole job, plus
+  * "roofline": the dominant kernel's algorithmic TFLOP/s against the bf16 MFMA peak, its
+    average duration taken live with HIP events on the launch stream;
+  * "cpu_baseline": the fp64 oracle (oracle/, untuned) timed on this machine's host cores on a
+    stated sample of the same workload.
+Only one GPU is used; --gpus N with N > 1 exits with a message.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_F32_VALU_TFLOPS = 157.3   # MI355X fp32 vector, published
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def flops_per_token_head(d, r, C):
+    """Algorithmic (masked, useful) FLOPs per token-head of the chunked algorithm, split by kernel.
+    flow: Gram d r^2 (C-1) + solve for [W|U'] 2 d r^2 (C-1) + masked Q K^T d r (C+1)
+    scan: W S^T, U_eff^T K, Q S^T = (4r+2) d^2, and P U_eff = d r (C+1)."""
+    flow = 3 * d * r * r * (C - 1) + d * r * (C + 1)
+    scan = (4 * r + 2) * d * d + d * r * (C + 1)
+    return flow, scan
+
+
+def min_bytes_per_token_head(d, r, e):
+    """Read q, r k, r v, r beta; write o."""
+    return e * d * (2 + 2 * r) + e * r
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2",
+                    help="cfg0..cfg4, cfg3a (see paper_2504_00492_amd/synth.py); cfg3b has no instance yet")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (one MI355X per box); "
+              f"--gpus {args.gpus} is not supported. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2504_00492_amd import binding as pf, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(3)
+    w = synth.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    dt = pf.PF_BF16 if w.dtype == "bf16" else pf.PF_F32
+    fam = pf.pf_delta_fwd_supported(w.d_k, w.d_v, w.r, w.chunk, dt)
+    if fam == 0:
+        print(f"bench.py: no kernel instance for workload {w.name}", file=sys.stderr)
+        sys.exit(4)
+
+    # ---- inputs: generated head by head on the host, uploaded once, resident before timing
+    B, H, L, r, dk, dv, C = w.B, w.H, w.L, w.r, w.d_k, w.d_v, w.chunk
+    Q = torch.empty((B * H, L, dk), dtype=tdt, device=dev)
+    K = torch.empty((B * H, L, r, dk), dtype=tdt, device=dev)
+    V = torch.empty((B * H, L, r, dv), dtype=tdt, device=dev)
+    beta = torch.empty((B * H, L, r), dtype=tdt, device=dev)
+    S0 = torch.empty((B * H, dv, dk), dtype=torch.float32, device=dev) if w.s0_std > 0 else None
+    for h in range(B * H):
+        q, k, v, b, s0 = synth.head_inputs(w, h)
+        Q[h] = torch.from_numpy(q).to(dev).to(tdt)
+        K[h] = torch.from_numpy(k).to(dev).to(tdt)
+        V[h] = torch.from_numpy(v).to(dev).to(tdt)
+        beta[h] = torch.from_numpy(b).to(dev).to(tdt)
+        if S0 is not None:
+            S0[h] = torch.from_numpy(s0).to(dev)
+    shp = lambda t: t.reshape((B, H) + tuple(t.shape[1:]))
+    Q, K, V, beta = shp(Q), shp(K), shp(V), shp(beta)
+    S0 = None if S0 is None else shp(S0)
+    O = torch.empty((B, H, L, dv), dtype=tdt, device=dev)
+    SL = torch.empty((B, H, dv, dk), dtype=torch.float32, device=dev)
+    need = pf.pf_delta_fwd_workspace_bytes(B, H, L, dk, dv, r, C, dt)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        st = pf.pf_delta_fwd(Q, K, V, beta, S0, O, SL, B, H, L, dk, dv, r, C, dt, ws, need, stream)
+        if st != pf.PF_OK:
+            raise pf.PfError(st, "pf_delta_fwd")
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens = B * L
+    token_heads = B * H * L
+    tok_per_s = tokens / (ms_per_step * 1e-3)
+
+    f_flow, f_scan = flops_per_token_head(dk, r, C)
+    e = 2 if w.dtype == "bf16" else 4
+    min_bytes = min_bytes_per_token_head(dk, r, e) * token_heads
+
+    # ---- per-kernel durations, HIP events on the launch stream (same kernels, same arguments)
+    kernels = {}
+    if fam == 2:
+        n = C * r
+        NC = L // C
+        mk = lambda *s: torch.empty(s, dtype=torch.bfloat16, device=dev)
+        Wn, UpT, KT, P = mk(B, H, NC, n, dk), mk(B, H, NC, dv, n), mk(B, H, NC, dk, n), mk(B, H, NC, C, n)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        for i in range(args.warmup + args.steps):
+            j = i - args.warmup
+            if j >= 0:
+                ev[j][0].record(stream)
+            st = pf.pf_delta_chunk_flow(Q, K, V, beta, Wn, UpT, KT, P, B, H, L, dk, dv, r, C, stream)
+            assert st == pf.PF_OK, st
+            if j >= 0:
+                ev[j][1].record(stream)
+            st = pf.pf_delta_chunk_scan(Q, Wn, UpT, KT, P, S0, O, SL, B, H, L, dk, dv, r, C, stream)
+            assert st == pf.PF_OK, st
+            if j >= 0:
+                ev[j][2].record(stream)
+        torch.cuda.synchronize()
+        t_flow = sum(a.elapsed_time(b) for a, b, _ in ev) / args.steps
+        t_scan = sum(b.elapsed_time(c) for _, b, c in ev) / args.steps
+        kernels = {
+            "flow_kernel": {"ms": t_flow, "alg_tflops": f_flow * token_heads / (t_flow * 1e-3) / 1e12},
+            "scan_kernel": {"ms": t_scan, "alg_tflops": f_scan * token_heads / (t_scan * 1e-3) / 1e12},
+        }
+        dom = "flow_kernel" if t_flow >= t_scan else "scan_kernel"
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": kernels[dom]["alg_tflops"],
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": kernels[dom]["alg_tflops"] / PEAK_BF16_TFLOPS,
+                    "avg_kernel_ms": kernels[dom]["ms"], "traffic": None}
+    else:
+        tfl = (f_flow + f_scan) * token_heads / (ms_per_step * 1e-3) / 1e12
+        roofline = {"bound": "alu", "kernel": "generic_kernel", "achieved": tfl, "peak": PEAK_F32_VALU_TFLOPS,
+                    "unit": "TFLOP/s", "frac": tfl / PEAK_F32_VALU_TFLOPS, "avg_kernel_ms": ms_per_step,
+                    "traffic": None}
+    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            roofline["traffic"] = json.load(open(traffic_file)).get(w.name, {}).get(roofline["kernel"])
+        except Exception:
+            pass
+
+    alg_tflops = (f_flow + f_scan) * token_heads / (ms_per_step * 1e-3) / 1e12
+    out = {
+        "metric": "tokens/s, chunked rank-r DeltaNet fwd, 1 MI355X",
+        "value": tok_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={B} H={H} L={L} d_k=d_v={dk} r={r} chunk={C} {w.dtype}",
+                   "kernel_family": {1: "generic", 2: "mfma"}[fam]},
+        "alg_tflops": alg_tflops, "frac_bf16_mfma_peak": alg_tflops / PEAK_BF16_TFLOPS,
+        "token_heads_per_s": token_heads / (ms_per_step * 1e-3),
+        "min_hbm_gbs": min_bytes / (ms_per_step * 1e-3) / 1e9,
+        "frac_hbm_peak_min_traffic": min_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "kernels": kernels, "roofline": roofline,
+    }
+
+    # ---- the oracle on the host cores, on a bounded sample of the same workload, plus parity on it
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = min(oracle.max_threads(), os.cpu_count() or 1)
+        per_head_flop = (4 * r + 2) * dv * dk * L
+        budget_flop = 8e9 * cores            # about ten seconds of this oracle per core
+        nh = int(max(1, min(B * H, budget_flop // per_head_flop)))
+        heads = list(range(nh))
+        inp = synth.make_inputs(w, heads)
+        tc0 = time.perf_counter()
+        Oref, SLref = oracle.delta_fwd(inp["Q"], inp["K"], inp["V"], inp["beta"], inp["S0"], nthreads=cores)
+        tc = time.perf_counter() - tc0
+        Og = O.reshape(B * H, L, dv)[:nh].float().cpu().numpy().astype(np.float64)
+        Sg = SL.reshape(B * H, dv, dk)[:nh].cpu().numpy().astype(np.float64)
+        rel = lambda x, ref: float(np.linalg.norm(x - ref) / max(np.linalg.norm(ref), 1e-300))
+        out["cpu_baseline"] = {
+            "value": (nh * L / H) / tc, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"{nh} of {B * H} (b,h) heads, full L={L}, fp64 token-by-token recurrence; "
+                      f"{tc:.2f} s wall; tokens/s scaled as token-heads/s / H",
+            "token_heads_per_s": nh * L / tc,
+        }
+        out["parity_on_sample"] = {"rel_l2_O": rel(Og, Oref), "rel_l2_S_L": rel(Sg, SLref),
+                                   "norm_S_L": float(np.linalg.norm(SLref)), "max_abs_O": float(np.abs(Oref).max())}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
