@@ -71,14 +71,65 @@ __global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Q, c
         }
     __syncthreads();
 
+    // Operands that do not depend on the state (W, U', Q, P, K^T of a chunk) are fetched one
+    // chunk ahead, straight into the MFMA operand registers: each set is refilled for chunk
+    // c+1 right after its last use in chunk c, so the loads fly under the rest of the step.
+    constexpr int M1 = N / 64;         // 16-row tiles of U_eff per wave
+    constexpr int T2 = (C / 16 + 3) / 4;   // 16-token tiles of O per wave
+    constexpr int NKT = N / 32;        // k-steps over the chunk's virtual tokens
+    bf16x8 a1[M1][NKS];
+    bf16x4 u1[M1][NNT];
+    bf16x8 q2[T2][NKS];
+    bf16x8 p2[T2][NKT];
+    bf16x8 k3[MPW][NKT];
+
+    auto load1 = [&](size_t cid) {
+        const bf16 *Wc = Wneg + cid * (size_t)N * D;
+        const bf16 *Uc = UpT + cid * (size_t)N * D;
+#pragma unroll
+        for (int i = 0; i < M1; ++i) {
+            const int mt = w + 4 * i;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) a1[i][ks] = ld8(Wc + (size_t)(16 * mt + r16) * D + 32 * ks + 8 * g);
+#pragma unroll
+            for (int nt = 0; nt < NNT; ++nt) u1[i][nt] = ld4(Uc + (size_t)(dv0 + 16 * nt + r16) * N + 16 * mt + 4 * g);
+        }
+    };
+    auto load2 = [&](size_t cid) {
+        const bf16 *Pc = P + cid * (size_t)C * N;
+        const bf16 *Qc = Q + cid * (size_t)C * D;
+#pragma unroll
+        for (int i = 0; i < T2; ++i) {
+            const int tt = w + 4 * i;
+            if (tt < C / 16) {
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks) q2[i][ks] = ld8(Qc + (size_t)(16 * tt + r16) * D + 32 * ks + 8 * g);
+                const int ksteps = (R * (16 * tt + 16) + 31) / 32;   // causal: virtual tokens < R (16 tt + 16)
+#pragma unroll
+                for (int ks = 0; ks < NKT; ++ks)
+                    if (ks < ksteps) p2[i][ks] = ld8(Pc + (size_t)(16 * tt + r16) * N + 32 * ks + 8 * g);
+            }
+        }
+    };
+    auto load3 = [&](size_t cid) {
+        const bf16 *Kc = KT + cid * (size_t)N * D;
+#pragma unroll
+        for (int a = 0; a < MPW; ++a)
+#pragma unroll
+            for (int ks = 0; ks < NKT; ++ks)
+                k3[a][ks] = ld8(Kc + (size_t)(16 * (w * MPW + a) + r16) * N + 32 * ks + 8 * g);
+    };
+
+    if (NC > 0) {
+        load1(chain * (size_t)NC);
+        load2(chain * (size_t)NC);
+        load3(chain * (size_t)NC);
+    }
+
     for (int ch = 0; ch < NC; ++ch) {
         const int cur = ch & 1;
         const size_t cid = chain * (size_t)NC + ch;
-        const bf16 *Wc = Wneg + cid * (size_t)N * D;
-        const bf16 *Uc = UpT + cid * (size_t)N * D;
-        const bf16 *Kc = KT + cid * (size_t)N * D;
-        const bf16 *Pc = P + cid * (size_t)C * N;
-        const bf16 *Qc = Q + cid * (size_t)C * D;
+        const bool more = ch + 1 < NC;
         bf16 *Oc = O + cid * (size_t)C * D;
         const bf16 *Scur = Sb + cur * TV * SP;
 
@@ -89,61 +140,63 @@ __global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Q, c
             for (int nt = 0; nt < NNT; ++nt)
 #pragma unroll
                 for (int ks = 0; ks < NKS; ++ks) bS[nt][ks] = ld8(&Scur[(16 * nt + r16) * SP + 32 * ks + 8 * g]);
-            for (int mt = w; mt < N / 16; mt += 4) {
+#pragma unroll
+            for (int i = 0; i < M1; ++i) {
+                const int mt = w + 4 * i;
                 f32x4 acc[NNT];
-                bf16x8 a[NKS];
 #pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) a[ks] = ld8(Wc + (size_t)(16 * mt + r16) * D + 32 * ks + 8 * g);
-#pragma unroll
-                for (int nt = 0; nt < NNT; ++nt)
-                    acc[nt] = __builtin_convertvector(ld4(Uc + (size_t)(dv0 + 16 * nt + r16) * N + 16 * mt + 4 * g), f32x4);
+                for (int nt = 0; nt < NNT; ++nt) acc[nt] = __builtin_convertvector(u1[i][nt], f32x4);
 #pragma unroll
                 for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
-                    for (int nt = 0; nt < NNT; ++nt) acc[nt] = mfma16(a[ks], bS[nt][ks], acc[nt]);
+                    for (int nt = 0; nt < NNT; ++nt) acc[nt] = mfma16(a1[i][ks], bS[nt][ks], acc[nt]);
 #pragma unroll
                 for (int nt = 0; nt < NNT; ++nt) st4(&Ue[(16 * nt + r16) * UP + 16 * mt + 4 * g], cvt4(acc[nt]));
             }
         }
+        if (more) load1(cid + 1);
         __syncthreads();
 
         // ---- (2) O^T = S Q^T + U_eff^T P^T : token tiles dealt to the waves
-        for (int tt = w; tt < C / 16; tt += 4) {
-            f32x4 oacc[NNT];
 #pragma unroll
-            for (int md = 0; md < NNT; ++md) oacc[md] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int i = 0; i < T2; ++i) {
+            const int tt = w + 4 * i;
+            if (tt < C / 16) {
+                f32x4 oacc[NNT];
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) {
-                bf16x8 b = ld8(Qc + (size_t)(16 * tt + r16) * D + 32 * ks + 8 * g);
+                for (int md = 0; md < NNT; ++md) oacc[md] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+                    for (int md = 0; md < NNT; ++md)
+                        oacc[md] = mfma16(ld8(&Scur[(16 * md + r16) * SP + 32 * ks + 8 * g]), q2[i][ks], oacc[md]);
+                const int ksteps = (R * (16 * tt + 16) + 31) / 32;
+#pragma unroll
+                for (int ks = 0; ks < NKT; ++ks)
+                    if (ks < ksteps) {
+#pragma unroll
+                        for (int md = 0; md < NNT; ++md)
+                            oacc[md] = mfma16(ld8(&Ue[(16 * md + r16) * UP + 32 * ks + 8 * g]), p2[i][ks], oacc[md]);
+                    }
 #pragma unroll
                 for (int md = 0; md < NNT; ++md)
-                    oacc[md] = mfma16(ld8(&Scur[(16 * md + r16) * SP + 32 * ks + 8 * g]), b, oacc[md]);
+                    st4(Oc + (size_t)(16 * tt + r16) * D + dv0 + 16 * md + 4 * g, cvt4(oacc[md]));
             }
-            // causal: tokens <= 16 tt + 15 means virtual tokens < R (16 tt + 16)
-            const int ksteps = (R * (16 * tt + 16) + 31) / 32;
-            for (int ks = 0; ks < ksteps; ++ks) {
-                bf16x8 b = ld8(Pc + (size_t)(16 * tt + r16) * N + 32 * ks + 8 * g);
-#pragma unroll
-                for (int md = 0; md < NNT; ++md)
-                    oacc[md] = mfma16(ld8(&Ue[(16 * md + r16) * UP + 32 * ks + 8 * g]), b, oacc[md]);
-            }
-#pragma unroll
-            for (int md = 0; md < NNT; ++md)
-                st4(Oc + (size_t)(16 * tt + r16) * D + dv0 + 16 * md + 4 * g, cvt4(oacc[md]));
         }
+        if (more) load2(cid + 1);
 
         // ---- (3) S^T += K^T U_eff : this wave's d_k rows
-        for (int ks = 0; ks < N / 32; ++ks) {
+#pragma unroll
+        for (int ks = 0; ks < NKT; ++ks) {
             bf16x8 b[NNT];
 #pragma unroll
             for (int nt = 0; nt < NNT; ++nt) b[nt] = ld8(&Ue[(16 * nt + r16) * UP + 32 * ks + 8 * g]);
 #pragma unroll
-            for (int a = 0; a < MPW; ++a) {
-                bf16x8 ak = ld8(Kc + (size_t)(16 * (w * MPW + a) + r16) * N + 32 * ks + 8 * g);
+            for (int a = 0; a < MPW; ++a)
 #pragma unroll
-                for (int nt = 0; nt < NNT; ++nt) sacc[a][nt] = mfma16(ak, b[nt], sacc[a][nt]);
-            }
+                for (int nt = 0; nt < NNT; ++nt) sacc[a][nt] = mfma16(k3[a][ks], b[nt], sacc[a][nt]);
         }
+        if (more) load3(cid + 1);
         bf16 *Snext = Sb + (cur ^ 1) * TV * SP;
 #pragma unroll
         for (int a = 0; a < MPW; ++a)
