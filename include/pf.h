@@ -102,21 +102,34 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
 
 /*
  * Step 2 of Section 3 on its own ("parallel compute": the flow of every chunk, no dependence
- * between chunks), MFMA path only (pf_delta_fwd_supported(...) == 2).  With n = chunk * r and
- * NC = L / chunk, for every (b, h, c):
+ * between chunks), MFMA path only (pf_delta_fwd_supported(...) == 2).  With n = chunk * r,
+ * d = d_k = d_v and NC = L / chunk, for every (b, h, c):
  *
- *   Cmat  = Id + M (.) diag(beta) K K^T,  M[(t,i),(s,j)] = 1 iff s < t     (Theorem 3.2 in delta
- *           variables; Id - M (.) A B^T of the theorem)
- *   Wneg  [B, H, NC, n, d_k]   bf16  out   -Cmat^{-1} (beta (.) K)   = -W of Theorem 3.2
- *   UpT   [B, H, NC, d_v, n]   bf16  out   (Cmat^{-1} (beta (.) V))^T = -U^T of Theorem 3.2,
- *                                          stored feature-major (transposed)
- *   KT    [B, H, NC, d_k, n]   bf16  out   the chunk's keys, transposed
- *   P     [B, H, NC, chunk, n] bf16  out   Mbar (.) Q K^T, Mbar[t,(s,j)] = 1 iff s <= t
+ *   Cmat = Id + M (.) diag(beta) K K^T,  M[(t,i),(s,j)] = 1 iff s < t     (Theorem 3.2 in delta
+ *          variables; Id - M (.) A B^T of the theorem)
+ *   W    = Cmat^{-1} (beta (.) K)     [n, d]      W of Theorem 3.2
+ *   U'   = Cmat^{-1} (beta (.) V)     [n, d]      -U of Theorem 3.2
+ *   P    = Mbar (.) Q K^T             [chunk, n]  Mbar[t,(s,j)] = 1 iff s <= t (readout mask)
  *
- * Inputs as in pf_delta_fwd.  All four outputs are required.
+ * The five outputs hold -W, U', K, P and Q of each chunk, bf16, chunk after chunk in (b, h, c)
+ * order, each chunk stored as a sequence of 16-row MFMA operand tiles: 64 "lanes" x 8 (or 4)
+ * consecutive elements per tile, lane = 16 g + r16.  With MT = n/16, NKT = n/32, DT = d/16,
+ * NKS = d/32, CT = chunk/16:
+ *
+ *   Wt [B,H,NC][MT][NKS][64][8]   -W[16 mt + r16][32 ks + 8 g + e]
+ *   Ut [B,H,NC][MT][DT ][64][4]   U'[16 mt + 4 g + e][16 dt + r16]
+ *   Kt [B,H,NC][DT][NKT][64][8]   K[32 kt + 8 g + e][16 a + r16]
+ *   Pt [B,H,NC][CT][NKT][64][8]   P[16 tt + r16][32 kt + 4 g + e]           for e < 4,
+ *                                 P[16 tt + r16][32 kt + 16 + 4 g + (e - 4)] for e >= 4;
+ *                                 tiles with 32 kt >= r (16 tt + 16) lie wholly behind the mask
+ *                                 and are left unwritten
+ *   Qt [B,H,NC][CT][NKS][64][8]   Q[16 tt + r16][32 ks + 8 g + e]
+ *
+ * Element counts per (b, h): Wt, Ut, Kt: L*r*d; Pt: L*n; Qt: L*d.  Inputs as in pf_delta_fwd.
+ * All five outputs are required.
  */
 pf_status pf_delta_chunk_flow(const void *Q, const void *K, const void *V, const void *beta,
-                              void *Wneg, void *UpT, void *KT, void *P,
+                              void *Wt, void *Ut, void *Kt, void *Pt, void *Qt,
                               int B, int H, int L, int d_k, int d_v, int r, int chunk,
                               pf_stream stream);
 
@@ -128,10 +141,10 @@ pf_status pf_delta_chunk_flow(const void *Q, const void *K, const void *V, const
  *   O_c   = Q S_c^T + P U_eff      (discrete flow of Section 3.1 truncated at each token)
  *   S_c+1 = S_c + U_eff^T K        (S_1 of Theorem 3.2)
  *
- * Q, S0, O, S_L as in pf_delta_fwd (dt = PF_BF16).
+ * S0, O, S_L as in pf_delta_fwd (dt = PF_BF16).
  */
-pf_status pf_delta_chunk_scan(const void *Q, const void *Wneg, const void *UpT, const void *KT,
-                              const void *P, const float *S0, void *O, float *S_L,
+pf_status pf_delta_chunk_scan(const void *Wt, const void *Ut, const void *Kt, const void *Pt,
+                              const void *Qt, const float *S0, void *O, float *S_L,
                               int B, int H, int L, int d_k, int d_v, int r, int chunk,
                               pf_stream stream);
 

@@ -1,5 +1,5 @@
 // Chunk-flow kernel: step 2 of Section 3 of ParallelFlow (arXiv 2504.00492), "parallel
-// compute".  One workgroup (4 wavefronts) per (b, h, chunk); no dependence between chunks.
+// compute".  One workgroup (8 wavefronts) per (b, h, chunk); no dependence between chunks.
 //
 // In delta variables (Remark in Section 3.1: A = beta k, Atil = -beta v, B = -k) Theorem 3.2
 // reads, with n = chunk * r virtual tokens and M strict in time,
@@ -10,55 +10,65 @@
 // T_ii (32 x 32) comes from two 16 x 16 forward substitutions in fp32 on the vector ALU and
 // one block merge  T_21 = -T_22 G_21 T_11  on MFMA.
 //
-// Work split.  The 2 d right-hand-side columns are dealt to the 4 wavefronts (waves 0-1 the
-// key columns, waves 2-3 the value columns).  A wave keeps every finished X_j of its column
+// Work split.  The 2 d right-hand-side columns are dealt to the 8 wavefronts (waves 0-3 the
+// key columns, waves 4-7 the value columns).  A wave keeps every finished X_j of its column
 // slice in registers, already in MFMA B-operand form, so the substitution itself needs no
-// barrier and no LDS traffic for X.  G_ij and T_ii are built cooperatively and read by all
-// waves as A operands from LDS.  Gram blocks are computed transposed so that an accumulator
-// tile (4 consecutive j per lane) goes to row-major LDS with 8-byte writes.
+// LDS traffic for X.  G_ij and T_ii are built cooperatively and read by all waves as A
+// operands from LDS.  Gram blocks are computed transposed so that an accumulator tile (4
+// consecutive j per lane) goes to row-major LDS with 8-byte writes.  V blocks and Q are
+// fetched ahead of their use into registers.
 //
-// Outputs (bf16):  Wneg = -W  row-major [n][d];  UpT = U'^T [d][n];  KT = K^T [d][n];
-//                  P = Mbar (.) Q K^T  [chunk][n], Mbar inclusive in time (readout mask).
+// Outputs: the tiled operand arrays described in pf_layout.h.
 #include "pf_internal.h"
 #include "pf_common.cuh"
+#include "pf_layout.h"
 
 namespace pf {
 
-template <int D, int N>
+constexpr int kFlowThreads = 512;
+constexpr int kFlowWaves = kFlowThreads / 64;
+
+template <int D, int N, int C>
 struct FlowLds {
     static constexpr int NB = N / 32;       // 32-row blocks per chunk
-    static constexpr int KP = D + 8;        // pitch of K / V rows (bf16)
+    static constexpr int KP = D + 8;        // pitch of K / V / Q rows (bf16)
     static constexpr int GP = N + 8;        // pitch of a G block-row (bf16)
     static constexpr int TP = 40;           // pitch of a T_ii row (bf16)
     static constexpr int NP = 36;           // pitch of the fp32 scratch used to build T_ii
-    static constexpr int WP = D / 2 + 8;    // pitch of the per-wave W staging tile (bf16)
+    static constexpr int FW = D / 4;        // right-hand-side columns per wave
+    static constexpr int WP = FW + 8;       // pitch of the per-wave W staging tile (bf16)
     static constexpr size_t oKs = 0;
     static constexpr size_t oBs = oKs + (size_t)N * KP * 2;
     static constexpr size_t oTs = oBs + (size_t)N * 4;
-    static constexpr size_t oUn = oTs + (size_t)NB * 32 * TP * 2;       // union region
-    // union, phase "build T": fp32 scratch, one 32 x NP tile per wave
-    static constexpr size_t szNs = (size_t)4 * 32 * NP * 4;
-    // union, phase "substitute": V block (x2), G block-row (x2), W staging (2 waves)
+    static constexpr size_t oUn = oTs + (size_t)NB * 32 * TP * 2;       // region reused by phase
+    // phase "build T": fp32 scratch, one 32 x NP tile per wave
+    static constexpr size_t szNs = (size_t)kFlowWaves * 32 * NP * 4;
+    // phase "substitute": V block (x2), G block-row (x2), W staging (4 waves)
     static constexpr size_t oVs = oUn;
     static constexpr size_t oGs = oVs + (size_t)2 * 32 * KP * 2;
     static constexpr size_t oWs = oGs + (size_t)2 * 32 * GP * 2;
-    static constexpr size_t endS = oWs + (size_t)2 * 32 * WP * 2;
-    static constexpr size_t total = (endS > oUn + szNs) ? endS : oUn + szNs;
+    static constexpr size_t szS = oWs + (size_t)4 * 32 * WP * 2 - oUn;
+    // phase "P": the chunk's queries
+    static constexpr size_t szQ = (size_t)C * KP * 2;
+    static constexpr size_t szUn = szNs > szS ? (szNs > szQ ? szNs : szQ) : (szS > szQ ? szS : szQ);
+    static constexpr size_t total = oUn + szUn;
 };
 
 template <int D, int N, int C>
-__global__ __launch_bounds__(256) void flow_kernel(const bf16 *__restrict__ Q, const bf16 *__restrict__ K,
-                                                   const bf16 *__restrict__ V, const bf16 *__restrict__ beta,
-                                                   bf16 *__restrict__ Wneg, bf16 *__restrict__ UpT,
-                                                   bf16 *__restrict__ KT, bf16 *__restrict__ P)
+__global__ __launch_bounds__(kFlowThreads) void flow_kernel(
+    const bf16 *__restrict__ Q, const bf16 *__restrict__ K, const bf16 *__restrict__ V,
+    const bf16 *__restrict__ beta, bf16 *__restrict__ Wt, bf16 *__restrict__ Ut, bf16 *__restrict__ Kt,
+    bf16 *__restrict__ Pt, bf16 *__restrict__ Qt)
 {
-    using Ld = FlowLds<D, N>;
+    using Ld = FlowLds<D, N, C>;
     constexpr int R = N / C;          // rank: virtual tokens per token
     constexpr int NB = Ld::NB;
-    constexpr int NT = D / 32;        // 16-column tiles of the right-hand side per wave
-    constexpr int NKS = D / 32;       // k-steps of a contraction over d
+    constexpr int FW = Ld::FW;
+    constexpr int NT = FW / 16;       // 16-column tiles of the right-hand side per wave
+    constexpr int NKS = D / 32, NKT = N / 32, MT = N / 16, DT = D / 16, CT = C / 16;
     constexpr int KP = Ld::KP, GP = Ld::GP, TP = Ld::TP, NP = Ld::NP, WP = Ld::WP;
-    static_assert(32 % R == 0 && N % 32 == 0 && C % 16 == 0 && D % 32 == 0, "tile shapes");
+    constexpr int NTHR = kFlowThreads;
+    static_assert(32 % R == 0 && N % 32 == 0 && C % 16 == 0 && D % 64 == 0, "tile shapes");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16 *Ks = reinterpret_cast<bf16 *>(smem + Ld::oKs);
@@ -68,6 +78,7 @@ __global__ __launch_bounds__(256) void flow_kernel(const bf16 *__restrict__ Q, c
     bf16 *Vs = reinterpret_cast<bf16 *>(smem + Ld::oVs);
     bf16 *Gs = reinterpret_cast<bf16 *>(smem + Ld::oGs);
     bf16 *WsAll = reinterpret_cast<bf16 *>(smem + Ld::oWs);
+    bf16 *Qs = reinterpret_cast<bf16 *>(smem + Ld::oUn);
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63;
@@ -78,52 +89,69 @@ __global__ __launch_bounds__(256) void flow_kernel(const bf16 *__restrict__ Q, c
     const bf16 *Vg = V + cid * (size_t)N * D;
     const bf16 *bg = beta + cid * (size_t)N;
     const bf16 *Qg = Q + cid * (size_t)C * D;
-    bf16 *Wg = Wneg + cid * (size_t)N * D;
-    bf16 *Ug = UpT + cid * (size_t)N * D;
-    bf16 *KTg = KT + cid * (size_t)N * D;
-    bf16 *Pg = P + cid * (size_t)C * N;
+    bf16 *Wg = Wt + cid * (size_t)N * D;
+    bf16 *Ug = Ut + cid * (size_t)N * D;
+    bf16 *Ktg = Kt + cid * (size_t)N * D;
+    bf16 *Ptg = Pt + cid * (size_t)C * N;
+    bf16 *Qtg = Qt + cid * (size_t)C * D;
 
-    // ---------------------------------------------------------------- load K, beta
-    for (int v = tid; v < N * D / 8; v += 256) {
-        const int row = v / (D / 8), cg = v % (D / 8);
-        st8(&Ks[row * KP + cg * 8], ld8(Kg + (size_t)row * D + cg * 8));
+    // ---------------------------------------------------------------- loads
+    // Q and the first V block go to registers now and to LDS when their region is free.
+    constexpr int QV = (C * D / 8 + NTHR - 1) / NTHR;
+    bf16x8 qreg[QV];
+#pragma unroll
+    for (int q = 0; q < QV; ++q) {
+        const int v = tid + NTHR * q;
+        if (v < C * D / 8) qreg[q] = ld8(Qg + (size_t)v * 8);
     }
-    for (int i = tid; i < N; i += 256) bs[i] = (float)bg[i];
+    constexpr int VVEC = 32 * D / 8;   // 16-byte vectors in one 32-row block of V (<= NTHR)
+    static_assert(VVEC <= NTHR, "one V block per pass");
+    const int vrow = tid / (D / 8), vcg = tid % (D / 8);
+    bf16x8 vreg = zero8();
+    if (tid < VVEC) vreg = ld8(Vg + (size_t)tid * 8);
+    for (int v = tid; v < N * D / 8; v += NTHR) {
+        const int row = v / (D / 8), cg = v % (D / 8);
+        st8(&Ks[row * KP + cg * 8], ld8(Kg + (size_t)v * 8));
+    }
+    for (int i = tid; i < N; i += NTHR) bs[i] = (float)bg[i];
     __syncthreads();
 
-    // ---------------------------------------------------------------- K^T out
-    for (int idx = tid; idx < D * (N / 8); idx += 256) {
-        const int x = idx % D, tg = idx / D;
-        bf16x8 v;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = Ks[(8 * tg + e) * KP + x];
-        st8(KTg + (size_t)x * N + 8 * tg, v);
+    // ---------------------------------------------------------------- K^T tiles out
+    for (int it = w; it < DT * NKT; it += kFlowWaves) {
+        const int a = it / NKT, kt = it % NKT;
+        const bf16 *p = &Ks[(32 * kt + 8 * g + (r16 >> 2)) * KP + 16 * a + 4 * (r16 & 3)];
+        bf16x4 lo = lds_read_tr4(p), hi = lds_read_tr4(p + 4 * KP);
+        st8(Ktg + ((size_t)(a * NKT + kt) * 64 + lane) * 8, join(lo, hi));
     }
 
     // ---------------------------------------------------------------- T_ii for every 32-block
     {
         float *Ns = NsAll + w * 32 * NP;
-        for (int it = 0; it < (NB + 3) / 4; ++it) {
-            const int db = it * 4 + w;
+        for (int it = 0; it < (NB + kFlowWaves - 1) / kFlowWaves; ++it) {
+            const int db = it * kFlowWaves + w;
             const bool active = db < NB;
             if (active) {
                 // N_db = strict-in-time part of diag(beta) K K^T on the block, fp32, row-major
+                f32x4 acc[3];
+#pragma unroll
+                for (int t3 = 0; t3 < 3; ++t3) acc[t3] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks) {
+                    bf16x8 k0 = ld8(&Ks[(32 * db + r16) * KP + 32 * ks + 8 * g]);
+                    bf16x8 k1 = ld8(&Ks[(32 * db + 16 + r16) * KP + 32 * ks + 8 * g]);
+                    acc[0] = mfma16(k0, k0, acc[0]);   // rows 0-15,  cols 0-15
+                    acc[1] = mfma16(k1, k0, acc[1]);   // rows 16-31, cols 0-15
+                    acc[2] = mfma16(k1, k1, acc[2]);   // rows 16-31, cols 16-31
+                }
 #pragma unroll
                 for (int tile = 0; tile < 4; ++tile) {
                     const int mi = tile >> 1, ni = tile & 1;
-                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-                    if (!(mi == 0 && ni == 1)) {
-#pragma unroll
-                        for (int ks = 0; ks < NKS; ++ks) {
-                            bf16x8 a = ld8(&Ks[(32 * db + 16 * mi + r16) * KP + 32 * ks + 8 * g]);
-                            bf16x8 b = ld8(&Ks[(32 * db + 16 * ni + r16) * KP + 32 * ks + 8 * g]);
-                            acc = mfma16(a, b, acc);
-                        }
-                    }
 #pragma unroll
                     for (int jj = 0; jj < 4; ++jj) {
                         const int row = 16 * mi + 4 * g + jj, col = 16 * ni + r16;
-                        const float val = (col / R < row / R) ? acc[jj] * bs[32 * db + row] : 0.0f;
+                        float val = 0.0f;
+                        if (tile != 1 && (col / R < row / R))
+                            val = acc[tile == 0 ? 0 : tile - 1][jj] * bs[32 * db + row];
                         Ns[row * NP + col] = val;
                     }
                 }
@@ -184,39 +212,43 @@ __global__ __launch_bounds__(256) void flow_kernel(const bf16 *__restrict__ Q, c
     }
 
     // ---------------------------------------------------------------- block forward substitution
-    const bool isV = (w >> 1) != 0;        // waves 2,3 solve for U', waves 0,1 for W
-    const int cb = (w & 1) * (D / 2);      // first column of this wave's slice inside K or V
+    const bool isV = w >= 4;               // waves 4-7 solve for U', waves 0-3 for W
+    const int cb = (w & 3) * FW;           // first column of this wave's slice inside K or V
     bf16x8 X[NB][NT];                      // finished blocks of this wave's slice, B-operand form
 
-    auto produce = [&](int i, int buf) {
-        // V rows of block i
-        bf16 *Vb = Vs + buf * 32 * KP;
-        for (int v = tid; v < 32 * D / 8; v += 256) {
-            const int row = v / (D / 8), cg = v % (D / 8);
-            st8(&Vb[row * KP + cg * 8], ld8(Vg + (size_t)(32 * i + row) * D + cg * 8));
-        }
-        // -G_ij for every j < i, transposed product so that lanes hold 4 consecutive j
+    // -G_ij for every j < i, transposed product so that lanes hold 4 consecutive j.
+    auto gram_row = [&](int i, int buf) {
         bf16 *Gb = Gs + buf * 32 * GP;
         const int nh = w & 1;
         bf16x8 bk[NKS];
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) bk[ks] = ld8(&Ks[(32 * i + 16 * nh + r16) * KP + 32 * ks + 8 * g]);
         const float nbeta = -bs[32 * i + 16 * nh + r16];
-        for (int jt = (w >> 1); jt < 2 * i; jt += 2) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int jt = (w >> 1); jt < 2 * i; jt += 8) {
+            const bool two = jt + 4 < 2 * i;       // second tile of the pair exists
+            const int jt2 = two ? jt + 4 : jt;
+            f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks)
-                acc = mfma16(ld8(&Ks[(16 * jt + r16) * KP + 32 * ks + 8 * g]), bk[ks], acc);
-            st4(&Gb[(16 * nh + r16) * GP + 16 * jt + 4 * g], cvt4(acc * nbeta));
+            for (int ks = 0; ks < NKS; ++ks) {
+                acc0 = mfma16(ld8(&Ks[(16 * jt + r16) * KP + 32 * ks + 8 * g]), bk[ks], acc0);
+                acc1 = mfma16(ld8(&Ks[(16 * jt2 + r16) * KP + 32 * ks + 8 * g]), bk[ks], acc1);
+            }
+            st4(&Gb[(16 * nh + r16) * GP + 16 * jt + 4 * g], cvt4(acc0 * nbeta));
+            if (two) st4(&Gb[(16 * nh + r16) * GP + 16 * jt2 + 4 * g], cvt4(acc1 * nbeta));
         }
     };
 
-    produce(0, 0);
+    if (tid < VVEC) st8(&Vs[vrow * KP + vcg * 8], vreg);                   // V block 0
+    if (NB > 1 && tid < VVEC) vreg = ld8(Vg + (size_t)VVEC * 8 + (size_t)tid * 8);   // V block 1 in flight
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const int buf = i & 1;
-        if (i + 1 < NB) produce(i + 1, buf ^ 1);
+        if (i + 1 < NB) {
+            gram_row(i + 1, buf ^ 1);
+            if (tid < VVEC) st8(&Vs[(buf ^ 1) * 32 * KP + vrow * KP + vcg * 8], vreg);
+            if (i + 2 < NB && tid < VVEC) vreg = ld8(Vg + (size_t)(i + 2) * VVEC * 8 + (size_t)tid * 8);
+        }
 
         const bf16 *src = isV ? (Vs + buf * 32 * KP) : (Ks + 32 * i * KP);
         const bf16 *Gb = Gs + buf * 32 * GP;
@@ -265,14 +297,14 @@ __global__ __launch_bounds__(256) void flow_kernel(const bf16 *__restrict__ Q, c
         for (int nt = 0; nt < NT; ++nt) X[i][nt] = join(cvt4(xacc[0][nt]), cvt4(xacc[1][nt]));
 
         if (isV) {
-            // U'^T: 4 consecutive tokens of one feature = one 8-byte store
+            // U' tiles are accumulator tiles as they stand: one contiguous 512 B store each
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt)
-                    st4(Ug + (size_t)(cb + 16 * nt + r16) * N + 32 * i + 16 * mi + 4 * g, cvt4(xacc[mi][nt]));
+                    st4(Ug + ((size_t)((2 * i + mi) * DT + cb / 16 + nt) * 64 + lane) * 4, cvt4(xacc[mi][nt]));
         } else {
-            // -W row-major: transpose the 32 x (d/2) tile through a wave-private LDS tile
+            // -W as A-operand tiles: transpose the 32 x FW tile through a wave-private LDS tile
             bf16 *Ws = WsAll + w * 32 * WP;
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
@@ -283,34 +315,50 @@ __global__ __launch_bounds__(256) void flow_kernel(const bf16 *__restrict__ Q, c
                     for (int jj = 0; jj < 4; ++jj) Ws[(16 * mi + 4 * g + jj) * WP + 16 * nt + r16] = v[jj];
                 }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            const int row = lane >> 1, half = lane & 1;
+            // this wave's columns are features [cb, cb + FW); lane (r16, g) of k-step ks holds
+            // features 32 ks + 8 g .. + 7
+            const int ks = cb / 32, fo = cb % 32;
+            if (8 * g >= fo && 8 * g < fo + FW) {
 #pragma unroll
-            for (int q = 0; q < D / 32; ++q)
-                st8(Wg + (size_t)(32 * i + row) * D + cb + half * (D / 4) + 8 * q,
-                    ld8(&Ws[row * WP + half * (D / 4) + 8 * q]));
+                for (int mi = 0; mi < 2; ++mi)
+                    st8(Wg + ((size_t)((2 * i + mi) * NKS + ks) * 64 + lane) * 8,
+                        ld8(&Ws[(16 * mi + r16) * WP + 8 * g - fo]));
+            }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
         __syncthreads();
     }
 
-    // ---------------------------------------------------------------- P = Mbar (.) Q K^T
-    for (int tt = w; tt < C / 16; tt += 4) {
+    // ---------------------------------------------------------------- P = Mbar (.) Q K^T, Q tiles
+#pragma unroll
+    for (int q = 0; q < QV; ++q) {
+        const int v = tid + NTHR * q;
+        if (v < C * D / 8) st8(&Qs[(v / (D / 8)) * KP + (v % (D / 8)) * 8], qreg[q]);
+    }
+    __syncthreads();
+    for (int it = w; it < CT * NKT; it += kFlowWaves) {
+        const int tt = it / NKT, kt = it % NKT;
+        if (32 * kt >= R * (16 * tt + 16)) continue;       // wholly after the last visible token
         bf16x8 bq[NKS];
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) bq[ks] = ld8(Qg + (size_t)(16 * tt + r16) * D + 32 * ks + 8 * g);
-        const int t = 16 * tt + r16;
-        for (int jt = 0; jt < N / 16; ++jt) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            if ((16 * jt) / R <= 16 * tt + 15) {
+        for (int ks = 0; ks < NKS; ++ks) bq[ks] = ld8(&Qs[(16 * tt + r16) * KP + 32 * ks + 8 * g]);
+        if (kt == 0) {
 #pragma unroll
-                for (int ks = 0; ks < NKS; ++ks)
-                    acc = mfma16(ld8(&Ks[(16 * jt + r16) * KP + 32 * ks + 8 * g]), bq[ks], acc);
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj)
-                    if ((16 * jt + 4 * g + jj) / R > t) acc[jj] = 0.0f;
-            }
-            st4(Pg + (size_t)t * N + 16 * jt + 4 * g, cvt4(acc));
+            for (int ks = 0; ks < NKS; ++ks) st8(Qtg + ((size_t)(tt * NKS + ks) * 64 + lane) * 8, bq[ks]);
         }
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            acc0 = mfma16(ld8(&Ks[(32 * kt + r16) * KP + 32 * ks + 8 * g]), bq[ks], acc0);
+            acc1 = mfma16(ld8(&Ks[(32 * kt + 16 + r16) * KP + 32 * ks + 8 * g]), bq[ks], acc1);
+        }
+        const int t = 16 * tt + r16;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            if ((32 * kt + 4 * g + jj) / R > t) acc0[jj] = 0.0f;
+            if ((32 * kt + 16 + 4 * g + jj) / R > t) acc1[jj] = 0.0f;
+        }
+        st8(Ptg + ((size_t)(tt * NKT + kt) * 64 + lane) * 8, join(cvt4(acc0), cvt4(acc1)));
     }
 }
 
@@ -329,32 +377,32 @@ bool mfma_instance_exists(int d, int n, int chunk)
 
 template <int D, int N, int C>
 static hipError_t launch_flow_instance(const void *Q, const void *K, const void *V, const void *beta,
-                                       void *Wneg, void *UpT, void *KT, void *P, size_t nchunks,
+                                       void *Wt, void *Ut, void *Kt, void *Pt, void *Qt, size_t nchunks,
                                        hipStream_t stream)
 {
     auto kern = flow_kernel<D, N, C>;
-    constexpr size_t lds = FlowLds<D, N>::total;
+    constexpr size_t lds = FlowLds<D, N, C>::total;
     static_assert(lds <= kMaxLdsBytes, "flow kernel LDS plan exceeds the CU");
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)nchunks), dim3(256), lds, stream, (const bf16 *)Q,
-                       (const bf16 *)K, (const bf16 *)V, (const bf16 *)beta, (bf16 *)Wneg, (bf16 *)UpT,
-                       (bf16 *)KT, (bf16 *)P);
+    hipLaunchKernelGGL(kern, dim3((unsigned)nchunks), dim3(kFlowThreads), lds, stream, (const bf16 *)Q,
+                       (const bf16 *)K, (const bf16 *)V, (const bf16 *)beta, (bf16 *)Wt, (bf16 *)Ut,
+                       (bf16 *)Kt, (bf16 *)Pt, (bf16 *)Qt);
     return hipGetLastError();
 }
 
-hipError_t launch_chunk_flow(const void *Q, const void *K, const void *V, const void *beta, void *Wneg,
-                             void *UpT, void *KT, void *P, int heads, int L, int d, int r, int chunk,
-                             hipStream_t stream)
+hipError_t launch_chunk_flow(const void *Q, const void *K, const void *V, const void *beta, void *Wt,
+                             void *Ut, void *Kt, void *Pt, void *Qt, int heads, int L, int d, int r,
+                             int chunk, hipStream_t stream)
 {
     const size_t nchunks = (size_t)heads * (L / chunk);
     if (nchunks == 0) return hipSuccess;
     if (nchunks > 0x7fffffffull) return hipErrorInvalidValue;
     const int n = chunk * r;
-#define X(DD, NN, CC)                                                                              \
-    if (d == DD && n == NN && chunk == CC)                                                          \
-        return launch_flow_instance<DD, NN, CC>(Q, K, V, beta, Wneg, UpT, KT, P, nchunks, stream);
+#define X(DD, NN, CC)                                                                                 \
+    if (d == DD && n == NN && chunk == CC)                                                             \
+        return launch_flow_instance<DD, NN, CC>(Q, K, V, beta, Wt, Ut, Kt, Pt, Qt, nchunks, stream);
     PF_FLOW_INSTANCES(X)
 #undef X
     return hipErrorInvalidValue;

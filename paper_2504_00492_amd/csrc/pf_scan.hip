@@ -6,16 +6,19 @@
 //     U_eff = U' - W S_c^T            n x TV      (U + W S_0^T of Theorem 3.2, sign folded)
 //     O_c   = Q S_c^T + P U_eff       chunk x TV  (discrete flow of Section 3.1 cut at each t)
 //     S_c+1 = S_c + U_eff^T K         TV x d      (S_1 of Theorem 3.2)
-// with W, U', K^T, P as written by the chunk-flow kernel.
+// with W, U', K^T, P and Q as written by the chunk-flow kernel (tiled operand arrays, see
+// pf_layout.h).
 //
 // Data movement.  S^T lives in fp32 accumulators (wave w owns d_k rows [w d/4, (w+1) d/4));
 // a bf16 copy in LDS ([d_v][d_k], double buffered) feeds the MFMA operands of the next chunk.
 // U_eff goes through LDS once ([d_v][n]: accumulator tiles are 4 consecutive tokens of one
 // feature, i.e. 8-byte writes).  W, K^T, Q and P are each used by exactly one wave, so they
-// are loaded straight from global memory into MFMA operand registers.  O is computed
-// transposed (rows = d_v) so that a lane ends up with 4 consecutive features of one token.
+// are loaded straight from global memory into MFMA operand registers, one contiguous tile per
+// load, one chunk ahead of their use.  O is computed transposed (rows = d_v) so that a lane
+// ends up with 4 consecutive features of one token.
 #include "pf_internal.h"
 #include "pf_common.cuh"
+#include "pf_layout.h"
 
 namespace pf {
 
@@ -29,9 +32,9 @@ struct ScanLds {
 };
 
 template <int D, int N, int C, int TV>
-__global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Q, const bf16 *__restrict__ Wneg,
-                                                   const bf16 *__restrict__ UpT, const bf16 *__restrict__ KT,
-                                                   const bf16 *__restrict__ P, const float *S0,
+__global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Wt, const bf16 *__restrict__ Ut,
+                                                   const bf16 *__restrict__ Kt, const bf16 *__restrict__ Pt,
+                                                   const bf16 *__restrict__ Qt, const float *S0,
                                                    bf16 *__restrict__ O, float *SL, int nchains, int NC)
 {
     using Ld = ScanLds<D, N, TV>;
@@ -39,6 +42,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Q, c
     constexpr int NKS = D / 32;        // k-steps over d
     constexpr int NNT = TV / 16;       // 16-wide tiles over this workgroup's d_v rows
     constexpr int MPW = D / 64;        // d_k tiles (16 rows of S^T) owned by one wave
+    constexpr int DT = D / 16;
     constexpr int SP = Ld::SP, UP = Ld::UP;
     static_assert(D % 64 == 0 && TV % 16 == 0 && N % 32 == 0 && C % 16 == 0, "tile shapes");
 
@@ -84,40 +88,40 @@ __global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Q, c
     bf16x8 k3[MPW][NKT];
 
     auto load1 = [&](size_t cid) {
-        const bf16 *Wc = Wneg + cid * (size_t)N * D;
-        const bf16 *Uc = UpT + cid * (size_t)N * D;
+        const bf16 *Wc = Wt + cid * (size_t)N * D;
+        const bf16 *Uc = Ut + cid * (size_t)N * D;
 #pragma unroll
         for (int i = 0; i < M1; ++i) {
             const int mt = w + 4 * i;
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) a1[i][ks] = ld8(Wc + (size_t)(16 * mt + r16) * D + 32 * ks + 8 * g);
+            for (int ks = 0; ks < NKS; ++ks) a1[i][ks] = ld8(Wc + ((size_t)(mt * NKS + ks) * 64 + lane) * 8);
 #pragma unroll
-            for (int nt = 0; nt < NNT; ++nt) u1[i][nt] = ld4(Uc + (size_t)(dv0 + 16 * nt + r16) * N + 16 * mt + 4 * g);
+            for (int nt = 0; nt < NNT; ++nt) u1[i][nt] = ld4(Uc + ((size_t)(mt * DT + dv0 / 16 + nt) * 64 + lane) * 4);
         }
     };
     auto load2 = [&](size_t cid) {
-        const bf16 *Pc = P + cid * (size_t)C * N;
-        const bf16 *Qc = Q + cid * (size_t)C * D;
+        const bf16 *Pc = Pt + cid * (size_t)C * N;
+        const bf16 *Qc = Qt + cid * (size_t)C * D;
 #pragma unroll
         for (int i = 0; i < T2; ++i) {
             const int tt = w + 4 * i;
             if (tt < C / 16) {
 #pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) q2[i][ks] = ld8(Qc + (size_t)(16 * tt + r16) * D + 32 * ks + 8 * g);
+                for (int ks = 0; ks < NKS; ++ks) q2[i][ks] = ld8(Qc + ((size_t)(tt * NKS + ks) * 64 + lane) * 8);
                 const int ksteps = (R * (16 * tt + 16) + 31) / 32;   // causal: virtual tokens < R (16 tt + 16)
 #pragma unroll
                 for (int ks = 0; ks < NKT; ++ks)
-                    if (ks < ksteps) p2[i][ks] = ld8(Pc + (size_t)(16 * tt + r16) * N + 32 * ks + 8 * g);
+                    if (ks < ksteps) p2[i][ks] = ld8(Pc + ((size_t)(tt * NKT + ks) * 64 + lane) * 8);
             }
         }
     };
     auto load3 = [&](size_t cid) {
-        const bf16 *Kc = KT + cid * (size_t)N * D;
+        const bf16 *Kc = Kt + cid * (size_t)N * D;
 #pragma unroll
         for (int a = 0; a < MPW; ++a)
 #pragma unroll
             for (int ks = 0; ks < NKT; ++ks)
-                k3[a][ks] = ld8(Kc + (size_t)(16 * (w * MPW + a) + r16) * N + 32 * ks + 8 * g);
+                k3[a][ks] = ld8(Kc + ((size_t)((w * MPW + a) * NKT + ks) * 64 + lane) * 8);
     };
 
     if (NC > 0) {
@@ -176,7 +180,9 @@ __global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Q, c
                     if (ks < ksteps) {
 #pragma unroll
                         for (int md = 0; md < NNT; ++md)
-                            oacc[md] = mfma16(ld8(&Ue[(16 * md + r16) * UP + 32 * ks + 8 * g]), p2[i][ks], oacc[md]);
+                            oacc[md] = mfma16(join(ld4(&Ue[(16 * md + r16) * UP + 32 * ks + 4 * g]),
+                                                   ld4(&Ue[(16 * md + r16) * UP + 32 * ks + 16 + 4 * g])),
+                                              p2[i][ks], oacc[md]);
                     }
 #pragma unroll
                 for (int md = 0; md < NNT; ++md)
@@ -222,21 +228,21 @@ __global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Q, c
     X(128, 64, 64) X(128, 128, 64) X(128, 128, 128) X(128, 256, 64) X(128, 256, 128)
 
 template <int D, int N, int C, int TV>
-static hipError_t launch_scan_instance(const void *Q, const void *Wneg, const void *UpT, const void *KT,
-                                       const void *P, const float *S0, void *O, float *SL, int heads,
+static hipError_t launch_scan_instance(const void *Wt, const void *Ut, const void *Kt, const void *Pt,
+                                       const void *Qt, const float *S0, void *O, float *SL, int heads,
                                        int NC, hipStream_t stream)
 {
     auto kern = scan_kernel<D, N, C, TV>;
     constexpr size_t lds = ScanLds<D, N, TV>::total;
     static_assert(lds <= 64 * 1024, "scan kernel is meant to leave room for several workgroups per CU");
     const unsigned grid = (unsigned)heads * (D / TV);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, (const bf16 *)Q, (const bf16 *)Wneg,
-                       (const bf16 *)UpT, (const bf16 *)KT, (const bf16 *)P, S0, (bf16 *)O, SL, heads, NC);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, (const bf16 *)Wt, (const bf16 *)Ut,
+                       (const bf16 *)Kt, (const bf16 *)Pt, (const bf16 *)Qt, S0, (bf16 *)O, SL, heads, NC);
     return hipGetLastError();
 }
 
-hipError_t launch_chunk_scan(const void *Q, const void *Wneg, const void *UpT, const void *KT,
-                             const void *P, const float *S0, void *O, float *SL, int heads, int L, int d,
+hipError_t launch_chunk_scan(const void *Wt, const void *Ut, const void *Kt, const void *Pt,
+                             const void *Qt, const float *S0, void *O, float *SL, int heads, int L, int d,
                              int r, int chunk, hipStream_t stream)
 {
     const int NC = L / chunk;
@@ -247,8 +253,8 @@ hipError_t launch_chunk_scan(const void *Q, const void *Wneg, const void *UpT, c
     const bool wide = (long long)heads * (d / 32) >= 256;
 #define X(DD, NN, CC)                                                                                   \
     if (d == DD && n == NN && chunk == CC)                                                               \
-        return wide ? launch_scan_instance<DD, NN, CC, 32>(Q, Wneg, UpT, KT, P, S0, O, SL, heads, NC, stream) \
-                    : launch_scan_instance<DD, NN, CC, 16>(Q, Wneg, UpT, KT, P, S0, O, SL, heads, NC, stream);
+        return wide ? launch_scan_instance<DD, NN, CC, 32>(Wt, Ut, Kt, Pt, Qt, S0, O, SL, heads, NC, stream) \
+                    : launch_scan_instance<DD, NN, CC, 16>(Wt, Ut, Kt, Pt, Qt, S0, O, SL, heads, NC, stream);
     PF_SCAN_INSTANCES(X)
 #undef X
     return hipErrorInvalidValue;

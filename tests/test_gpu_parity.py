@@ -80,32 +80,52 @@ def test_empty_sequence_returns_initial_state(pf):
 # ------------------------------------------------------------------ chunk flow (Theorem 3.2) on its own
 @pytest.mark.parametrize("d,r,C", [(64, 1, 64), (128, 2, 64), (128, 4, 64), (128, 2, 128), (128, 1, 128), (64, 4, 64)])
 def test_chunk_flow_matches_theorem(pf, oracle, d, r, C):
-    """W, U', K^T and P of every chunk against the numpy statement of Theorem 3.2."""
+    """W, U', K, P and Q of every chunk (decoded from their tiled layouts) against the numpy
+    statement of Theorem 3.2; then the scan entry point on those arrays against the oracle."""
     import torch
     from oracle import chunk_flow_ref as cf
+    from gpu_util import untile_rows8, untile_acc4
     w = synth.Workload("flow", "bf16", 1, 2, 2 * C, d, d, r, C, seed=21, reflect_frac=0.1)
     _say(f"[case] chunk flow d={d} r={r} C={C}")
     inp = synth.make_inputs(w)
     dev = to_device(w, inp)
     n, NC = C * r, w.L // C
-    mk = lambda *s: torch.empty(s, dtype=torch.bfloat16, device="cuda:0")
-    Wn, UpT, KT, P = mk(1, 2, NC, n, d), mk(1, 2, NC, d, n), mk(1, 2, NC, d, n), mk(1, 2, NC, C, n)
-    st = pf.pf_delta_chunk_flow(dev["Q"], dev["K"], dev["V"], dev["beta"], Wn, UpT, KT, P, 1, 2, w.L, d, d, r, C)
+    mk = lambda m: torch.full((1, 2, NC, m), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    Wt, Ut, Kt, Pt, Qt = mk(n * d), mk(n * d), mk(n * d), mk(C * n), mk(C * d)
+    st = pf.pf_delta_chunk_flow(dev["Q"], dev["K"], dev["V"], dev["beta"], Wt, Ut, Kt, Pt, Qt, 1, 2, w.L, d, d, r, C)
+    assert st == pf.PF_OK
+    O = torch.empty(1, 2, w.L, d, dtype=torch.bfloat16, device="cuda:0")
+    SL = torch.empty(1, 2, d, d, dtype=torch.float32, device="cuda:0")
+    st = pf.pf_delta_chunk_scan(Wt, Ut, Kt, Pt, Qt, None, O, SL, 1, 2, w.L, d, d, r, C)
     assert st == pf.PF_OK
     torch.cuda.synchronize()
-    Wn, UpT, KT, P = (t.float().cpu().numpy() for t in (Wn, UpT, KT, P))
+    Wt, Ut, Kt, Pt, Qt = (t.float().cpu().numpy() for t in (Wt, Ut, Kt, Pt, Qt))
+    MT, NKT, DT, NKS, CT = n // 16, n // 32, d // 16, d // 32, C // 16
     for h in range(2):
         for c in range(NC):
             sl = slice(c * C, (c + 1) * C)
             A, At, Bm = cf.delta_drivers(inp["K"][h, sl], inp["V"][h, sl], inp["beta"][h, sl])
             Wr, Ur = cf.chunk_flow(A, At, Bm)                     # paper's W and U (= -U')
             Kf = inp["K"][h, sl].reshape(n, d).astype(np.float64)
-            Pr = cf.inclusive_time_mask(C, r) * (inp["Q"][h, sl].astype(np.float64) @ Kf.T)
-            assert rel_l2(Wn[0, h, c], -Wr) < 1e-2
-            assert rel_l2(UpT[0, h, c].T, -Ur) < 1e-2
-            assert np.array_equal(KT[0, h, c].T, inp["K"][h, sl].reshape(n, d))
-            assert rel_l2(P[0, h, c], Pr) < 5e-3
-            assert np.all(P[0, h, c][cf.inclusive_time_mask(C, r) == 0] == 0)
+            mask = cf.inclusive_time_mask(C, r)
+            Pr = mask * (inp["Q"][h, sl].astype(np.float64) @ Kf.T)
+            Wg = untile_rows8(Wt[0, h, c], MT, NKS)
+            Ug = untile_acc4(Ut[0, h, c], MT, DT)
+            Kg = untile_rows8(Kt[0, h, c], DT, NKT).T
+            Qg = untile_rows8(Qt[0, h, c], CT, NKS)
+            Pg = untile_rows8(Pt[0, h, c], CT, NKT, relabel=True)
+            assert rel_l2(Wg, -Wr) < 1e-2
+            assert rel_l2(Ug, -Ur) < 1e-2
+            assert np.array_equal(Kg, inp["K"][h, sl].reshape(n, d))
+            assert np.array_equal(Qg, inp["Q"][h, sl])
+            # P: written tiles carry zeros behind the mask; tiles wholly behind it stay untouched (NaN)
+            written = ~np.isnan(Pg)
+            assert np.all(written[mask == 1])
+            assert np.all(Pg[written & (mask == 0)] == 0)
+            assert rel_l2(np.where(written, Pg, 0.0), Pr) < 5e-3
+    Oref, SLref = oracle.delta_fwd(inp["Q"], inp["K"], inp["V"], inp["beta"], None)
+    assert rel_l2(flat_heads(O.float().cpu().numpy()), Oref) < TOL["bf16"]
+    assert rel_l2(flat_heads(SL.cpu().numpy()), SLref) < TOL["bf16"]
 
 
 # ------------------------------------------------------------------ MFMA path, sizes the oracle does in seconds
