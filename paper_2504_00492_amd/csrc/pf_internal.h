@@ -7,7 +7,8 @@
 
 namespace pf {
 
-constexpr size_t kMaxLdsBytes = 160 * 1024;  // LDS per workgroup on gfx950
+constexpr size_t kMaxLdsBytes = 160 * 1024;  // LDS per workgroup (and per CU) on gfx950
+constexpr size_t kNumCUs = 256;              // compute units of one MI355X
 
 // ---- generic path (pf_generic.hip)
 size_t generic_lds_bytes(int dk, int dv, int r, int chunk);
