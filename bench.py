@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--workload", default="cfg2",
                     help="cfg0..cfg4, cfg3a (see paper_2504_00492_amd/synth.py); cfg3b has no instance yet")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seq-len", type=int, default=0, help="override the workload's L (experiments only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (one MI355X per box); "
@@ -64,6 +65,8 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         sys.exit(3)
     w = synth.WORKLOADS[args.workload]
+    if args.seq_len > 0:
+        w = w.with_(L=args.seq_len, name=f"{w.name}@L={args.seq_len}")
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32

@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
     constexpr int VR = KV > 4 ? 4 : KV;                // V travels through a ring of VR passes
     static_assert(KV % VR == 0, "ring slots are reused with a fixed stride");
     bf16x8 kreg[KV], vreg[VR], qreg[QV];
-    float breg = 0.0f;
+    bf16 breg = (bf16)0.0f;   // kept as loaded: converting here would wait for the fetch
 
     auto fetch_k = [&](size_t c) {
         const bf16 *Kg = K + c * (size_t)N * D;
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
             const int v = tid0 + NTHR * q;
             if ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8) kreg[q] = ld8(Kg + (size_t)v * 8);
         }
-        breg = (float)beta[c * (size_t)N + (tid0 % N)];   // every thread loads: no branch, always in range
+        breg = beta[c * (size_t)N + (tid0 % N)];   // every thread loads: no branch, always in range
     };
     auto fetch_v_pass = [&](size_t c, int q) {       // the blocks [q BPP, (q+1) BPP) of V
         const int v = tid0 + NTHR * q;
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
             const int v = tid + NTHR * q;
             if ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8) st8(&Ks[(v / VPR) * KP + (v % VPR) * 8], kreg[q]);
         }
-        if (tid < N) bs[tid] = breg;
+        if (tid < N) bs[tid] = (float)breg;
         // V block b: registers -> LDS buffer (b & 1).  When that frees a ring slot, the slot is
         // refilled with the pass VR further down the stream (this chunk's, then the next one's).
         auto stage_v = [&](int b) {
