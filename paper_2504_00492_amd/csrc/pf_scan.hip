@@ -16,39 +16,54 @@
 // are loaded straight from global memory into MFMA operand registers, one contiguous tile per
 // load, one chunk ahead of their use.  O is computed transposed (rows = d_v) so that a lane
 // ends up with 4 consecutive features of one token.
+//
+// Where the register budget allows a fifth wave (n <= 128), the four compute waves issue no
+// global stores inside the chunk loop: O tiles go to LDS and the fifth wave copies them out one
+// step later.  With only loads in flight, a wave's memory counter retires in order, so waiting
+// for one operand set does not also wait for the sets that were requested after it - which is
+// what keeps the one-chunk-ahead fetch ahead.  For n = 256 the operand sets need more than 256
+// registers per lane, which only four waves per workgroup leave room for; there the compute
+// waves store O themselves.
 #include "pf_internal.h"
 #include "pf_common.cuh"
 #include "pf_layout.h"
 
 namespace pf {
 
-template <int D, int N, int TV>
+constexpr int kScanComputeWaves = 4;
+template <int N> constexpr bool scan_has_writer() { return N <= 128; }
+template <int N> constexpr int scan_threads() { return 64 * (kScanComputeWaves + (scan_has_writer<N>() ? 1 : 0)); }
+
+template <int D, int N, int C, int TV>
 struct ScanLds {
     static constexpr int SP = D + 8;   // pitch of a row of the bf16 state copy
     static constexpr int UP = N + 8;   // pitch of a row of U_eff^T
+    static constexpr int OP = TV + 8;  // pitch of a row (one token) of the staged O tile
     static constexpr size_t oSb = 0;
     static constexpr size_t oUe = oSb + (size_t)2 * TV * SP * 2;
-    static constexpr size_t total = oUe + (size_t)TV * UP * 2;
+    static constexpr size_t oOb = oUe + (size_t)TV * UP * 2;
+    static constexpr size_t total = oOb + (scan_has_writer<N>() ? (size_t)2 * C * OP * 2 : 0);
 };
 
 template <int D, int N, int C, int TV>
-__global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Wt, const bf16 *__restrict__ Ut,
+__global__ __launch_bounds__(scan_threads<N>()) void scan_kernel(const bf16 *__restrict__ Wt, const bf16 *__restrict__ Ut,
                                                    const bf16 *__restrict__ Kt, const bf16 *__restrict__ Pt,
                                                    const bf16 *__restrict__ Qt, const float *S0,
                                                    bf16 *__restrict__ O, float *SL, int nchains, int NC)
 {
-    using Ld = ScanLds<D, N, TV>;
+    using Ld = ScanLds<D, N, C, TV>;
     constexpr int R = N / C;
     constexpr int NKS = D / 32;        // k-steps over d
     constexpr int NNT = TV / 16;       // 16-wide tiles over this workgroup's d_v rows
     constexpr int MPW = D / 64;        // d_k tiles (16 rows of S^T) owned by one wave
     constexpr int DT = D / 16;
-    constexpr int SP = Ld::SP, UP = Ld::UP;
+    constexpr int SP = Ld::SP, UP = Ld::UP, OP = Ld::OP;
     static_assert(D % 64 == 0 && TV % 16 == 0 && N % 32 == 0 && C % 16 == 0, "tile shapes");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16 *Sb = reinterpret_cast<bf16 *>(smem + Ld::oSb);
     bf16 *Ue = reinterpret_cast<bf16 *>(smem + Ld::oUe);
+    bf16 *Ob = reinterpret_cast<bf16 *>(smem + Ld::oOb);
 
     const int tid = threadIdx.x;
     const int w = tid >> 6, lane = tid & 63;
@@ -59,6 +74,28 @@ __global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Wt, 
     const int tile = blockIdx.x / nchains;
     const size_t chain = blockIdx.x % nchains;
     const int dv0 = tile * TV;
+
+    constexpr bool kWriter = scan_has_writer<N>();
+    if (kWriter && w == kScanComputeWaves) {
+        // ---- writer wave: after each step's closing barrier, copy that step's O tile
+        // (chunk tokens x TV features) from LDS to its rows of O.  It takes part in every
+        // barrier of the compute waves and touches nothing else.
+        constexpr int PPT = TV / 8;              // 16-byte pieces per token
+        constexpr int TPI = 64 / PPT;            // tokens per pass of the wave
+        __syncthreads();                         // pairs with the barrier after the initial state
+        for (int ch = 0; ch < NC; ++ch) {
+            __syncthreads();
+            __syncthreads();
+            const bf16 *src = Ob + (ch & 1) * C * OP;
+            bf16 *Oc = O + (chain * (size_t)NC + ch) * (size_t)C * D;
+#pragma unroll
+            for (int t0 = 0; t0 < C; t0 += TPI) {
+                const int t = t0 + lane / PPT, pc = lane % PPT;
+                st8(Oc + (size_t)t * D + dv0 + 8 * pc, ld8(&src[t * OP + 8 * pc]));
+            }
+        }
+        return;
+    }
 
     // ---- initial state: fp32 accumulators + bf16 copy
     f32x4 sacc[MPW][NNT];
@@ -99,19 +136,23 @@ __global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Wt, 
             for (int nt = 0; nt < NNT; ++nt) u1[i][nt] = ld4(Uc + ((size_t)(mt * DT + dv0 / 16 + nt) * 64 + lane) * 4);
         }
     };
+    static_assert((C / 16) % kScanComputeWaves == 0, "every compute wave owns the same number of token tiles");
     auto load2 = [&](size_t cid) {
         const bf16 *Pc = Pt + cid * (size_t)C * N;
         const bf16 *Qc = Qt + cid * (size_t)C * D;
 #pragma unroll
         for (int i = 0; i < T2; ++i) {
             const int tt = w + 4 * i;
-            if (tt < C / 16) {
 #pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) q2[i][ks] = ld8(Qc + ((size_t)(tt * NKS + ks) * 64 + lane) * 8);
-                const int ksteps = (R * (16 * tt + 16) + 31) / 32;   // causal: virtual tokens < R (16 tt + 16)
+            for (int ks = 0; ks < NKS; ++ks) q2[i][ks] = ld8(Qc + ((size_t)(tt * NKS + ks) * 64 + lane) * 8);
+            // Tiles behind the causal limit (32 ks >= R (16 tt + 16)) were never written and are
+            // never multiplied; their slots re-read tile 0 so that the load sequence has no
+            // branch (a branch here would make every later wait a full drain).
+            const int ksteps = (R * (16 * tt + 16) + 31) / 32;
 #pragma unroll
-                for (int ks = 0; ks < NKT; ++ks)
-                    if (ks < ksteps) p2[i][ks] = ld8(Pc + ((size_t)(tt * NKT + ks) * 64 + lane) * 8);
+            for (int ks = 0; ks < NKT; ++ks) {
+                const int kk = ks < ksteps ? ks : 0;
+                p2[i][ks] = ld8(Pc + ((size_t)(tt * NKT + kk) * 64 + lane) * 8);
             }
         }
     };
@@ -133,7 +174,10 @@ __global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Wt, 
     for (int ch = 0; ch < NC; ++ch) {
         const int cur = ch & 1;
         const size_t cid = chain * (size_t)NC + ch;
-        const bool more = ch + 1 < NC;
+        // The fetch for "the next chunk" is unconditional (the last step re-fetches its own chunk):
+        // a branch around it would force every later wait to assume the shorter queue.
+        const size_t nx = ch + 1 < NC ? cid + 1 : cid;
+        bf16 *Ocur = Ob + cur * C * OP;
         bf16 *Oc = O + cid * (size_t)C * D;
         const bf16 *Scur = Sb + cur * TV * SP;
 
@@ -158,14 +202,14 @@ __global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Wt, 
                 for (int nt = 0; nt < NNT; ++nt) st4(&Ue[(16 * nt + r16) * UP + 16 * mt + 4 * g], cvt4(acc[nt]));
             }
         }
-        if (more) load1(cid + 1);
+        load1(nx);
         __syncthreads();
 
         // ---- (2) O^T = S Q^T + U_eff^T P^T : token tiles dealt to the waves
 #pragma unroll
         for (int i = 0; i < T2; ++i) {
             const int tt = w + 4 * i;
-            if (tt < C / 16) {
+            {
                 f32x4 oacc[NNT];
 #pragma unroll
                 for (int md = 0; md < NNT; ++md) oacc[md] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -186,10 +230,11 @@ __global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Wt, 
                     }
 #pragma unroll
                 for (int md = 0; md < NNT; ++md)
-                    st4(Oc + (size_t)(16 * tt + r16) * D + dv0 + 16 * md + 4 * g, cvt4(oacc[md]));
+                    if (kWriter) st4(&Ocur[(16 * tt + r16) * OP + 16 * md + 4 * g], cvt4(oacc[md]));
+                    else st4(Oc + (size_t)(16 * tt + r16) * D + dv0 + 16 * md + 4 * g, cvt4(oacc[md]));
             }
         }
-        if (more) load2(cid + 1);
+        load2(nx);
 
         // ---- (3) S^T += K^T U_eff : this wave's d_k rows
 #pragma unroll
@@ -202,7 +247,7 @@ __global__ __launch_bounds__(256) void scan_kernel(const bf16 *__restrict__ Wt, 
 #pragma unroll
                 for (int nt = 0; nt < NNT; ++nt) sacc[a][nt] = mfma16(k3[a][ks], b[nt], sacc[a][nt]);
         }
-        if (more) load3(cid + 1);
+        load3(nx);
         bf16 *Snext = Sb + (cur ^ 1) * TV * SP;
 #pragma unroll
         for (int a = 0; a < MPW; ++a)
@@ -233,10 +278,10 @@ static hipError_t launch_scan_instance(const void *Wt, const void *Ut, const voi
                                        int NC, hipStream_t stream)
 {
     auto kern = scan_kernel<D, N, C, TV>;
-    constexpr size_t lds = ScanLds<D, N, TV>::total;
+    constexpr size_t lds = ScanLds<D, N, C, TV>::total;
     static_assert(lds <= 64 * 1024, "scan kernel is meant to leave room for several workgroups per CU");
     const unsigned grid = (unsigned)heads * (D / TV);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, (const bf16 *)Wt, (const bf16 *)Ut,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(scan_threads<N>()), lds, stream, (const bf16 *)Wt, (const bf16 *)Ut,
                        (const bf16 *)Kt, (const bf16 *)Pt, (const bf16 *)Qt, S0, (bf16 *)O, SL, heads, NC);
     return hipGetLastError();
 }
