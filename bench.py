@@ -51,6 +51,9 @@ def main():
                     help="cfg0..cfg4, cfg3a (see paper_2504_00492_amd/synth.py); cfg3b has no instance yet")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seq-len", type=int, default=0, help="override the workload's L (experiments only)")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="after the timed region, run a plain device-to-device copy of this many MiB "
+                         "(a kernel of known traffic to scale rocprofv3 FETCH_SIZE / WRITE_SIZE by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (one MI355X per box); "
@@ -165,6 +168,14 @@ def main():
             roofline["traffic"] = json.load(open(traffic_file)).get(w.name, {}).get(roofline["kernel"])
         except Exception:
             pass
+
+    if args.calibration_copy_mib > 0:
+        nbytes = args.calibration_copy_mib << 20
+        src = torch.ones(nbytes // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     alg_tflops = (f_flow + f_scan) * token_heads / (ms_per_step * 1e-3) / 1e12
     out = {

@@ -165,6 +165,72 @@ __global__ __launch_bounds__(scan_threads<N>()) void scan_kernel(const bf16 *__r
                 k3[a][ks] = ld8(Kc + ((size_t)((w * MPW + a) * NKT + ks) * 64 + lane) * 8);
     };
 
+    // ---- L2 warm-up.  A workgroup can only keep so many bytes in flight, so at HBM latency the
+    // demand loads above would be what bounds a step.  Two steps ahead of its use, every line of
+    // a chunk's operand arrays is touched once (one dword per 128-byte line); the tiles of one
+    // (b, h) share an L2 and split the lines among themselves, so this costs each wave a couple
+    // of load instructions per step and turns the demand loads into L2 hits.  The touched words
+    // are never looked at.
+    constexpr int kAhead = 2;
+    constexpr int NTILES = D / TV;
+    constexpr int kLine = 64;                                   // bf16 elements per 128-byte line
+    constexpr int LW = (N * D / kLine + NTILES - 1) / NTILES;   // lines of Wt (and of Kt) per tile
+    constexpr int LP = (C * N / kLine + NTILES - 1) / NTILES;   // lines of Pt per tile
+    constexpr int LQ = (C * D / kLine + NTILES - 1) / NTILES;   // lines of Qt per tile
+    constexpr int LU = N * TV / kLine;                          // lines of this tile's part of Ut
+    constexpr int LMAX = LW > LP ? (LW > LU ? LW : LU) : (LP > LU ? LP : LU);
+    // Measured: it pays for n = 256 (about 8 %), and costs a little for the smaller chunks.
+    constexpr bool kWarm = N >= 256;
+    constexpr int T0 = kWarm ? (LMAX + 63) / 64 : 0, T1 = kWarm ? (LQ + 63) / 64 : 0, NTOUCH = T0 + T1;
+    // wave 0: Wt, wave 1: Kt, wave 2: Pt, wave 3: this tile's Ut and (second job) Qt
+    const bf16 *tbase[NTOUCH + 1];
+    size_t tstride[NTOUCH + 1];
+    if (kWarm) {
+        const bf16 *b0 = w == 0 ? Wt : w == 1 ? Kt : w == 2 ? Pt : Ut;
+        const size_t st0 = w == 2 ? (size_t)C * N : (size_t)N * D;
+        const int total0 = w == 2 ? C * N / kLine : N * D / kLine;
+        const int cnt0 = w < 2 ? LW : w == 2 ? LP : LU;
+#pragma unroll
+        for (int k = 0; k < T0; ++k) {
+            int j = lane + 64 * k;
+            j = j < cnt0 ? j : cnt0 - 1;
+            size_t el;
+            if (w == 3) {   // Ut tiles of this d_v tile: [mt][dt][64 lanes][4]; TV*16 elements per mt
+                constexpr int per_mt = TV * 16 / kLine > 0 ? TV * 16 / kLine : 1;
+                el = (size_t)((j / per_mt) * DT + dv0 / 16) * 256 + (size_t)(j % per_mt) * kLine;
+            } else {
+                int line = tile * cnt0 + j;
+                line = line < total0 ? line : total0 - 1;
+                el = (size_t)line * kLine;
+            }
+            tbase[k] = b0 + chain * (size_t)NC * st0 + el;
+            tstride[k] = st0;
+        }
+#pragma unroll
+        for (int k = 0; k < T1; ++k) {
+            int j = lane + 64 * k;
+            j = j < LQ ? j : LQ - 1;
+            int line = tile * LQ + j;
+            line = line < C * D / kLine ? line : C * D / kLine - 1;
+            // only wave 3 has a second job; the others re-touch their own first line
+            tbase[T0 + k] = w == 3 ? Qt + chain * (size_t)NC * C * D + (size_t)line * kLine : tbase[0];
+            tstride[T0 + k] = w == 3 ? (size_t)C * D : tstride[0];
+        }
+    }
+    // The touched word is "used" by an empty asm statement one step later, just before the
+    // register is reloaded: late enough that the load has long returned, and enough to keep the
+    // compiler from dropping it.
+    uint32_t touched[NTOUCH + 1];
+#pragma unroll
+    for (int k = 0; k < NTOUCH; ++k) touched[k] = 0;
+    auto touch = [&](int c) {   // c = chunk index within this (b, h)
+#pragma unroll
+        for (int k = 0; k < NTOUCH; ++k) {
+            asm volatile("" ::"v"(touched[k]));
+            touched[k] = *reinterpret_cast<const uint32_t *>(tbase[k] + (size_t)c * tstride[k]);
+        }
+    };
+
     if (NC > 0) {
         load1(chain * (size_t)NC);
         load2(chain * (size_t)NC);
@@ -248,6 +314,7 @@ __global__ __launch_bounds__(scan_threads<N>()) void scan_kernel(const bf16 *__r
                 for (int nt = 0; nt < NNT; ++nt) sacc[a][nt] = mfma16(k3[a][ks], b[nt], sacc[a][nt]);
         }
         load3(nx);
+        touch(ch + kAhead < NC ? ch + kAhead : ch);
         bf16 *Snext = Sb + (cur ^ 1) * TV * SP;
 #pragma unroll
         for (int a = 0; a < MPW; ++a)
@@ -257,6 +324,8 @@ __global__ __launch_bounds__(scan_threads<N>()) void scan_kernel(const bf16 *__r
         __syncthreads();
     }
 
+#pragma unroll
+    for (int k = 0; k < NTOUCH; ++k) asm volatile("" ::"v"(touched[k]));
     if (SL) {
 #pragma unroll
         for (int a = 0; a < MPW; ++a)

@@ -1,0 +1,61 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times: the whole
+workload runs on the GPU through pf_delta_fwd, and a sample of (b, h) heads - each a complete
+recurrence over L tokens, which is the unit the oracle can compute on its own - is compared
+element by element with the fp64 oracle."""
+import numpy as np
+import pytest
+
+from paper_2504_00492_amd import synth
+from gpu_util import rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pf():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2504_00492_amd import binding
+    return binding
+
+
+@pytest.mark.parametrize("name,sample", [
+    ("cfg1", [0, 13, 31]),
+    ("cfg2", [0, 21, 63]),
+    ("cfg3a", [0, 17]),
+    ("cfg4", [5, 30]),
+])
+def test_full_size_sampled_heads(pf, oracle, name, sample):
+    import torch
+    w = synth.WORKLOADS[name]
+    print(f"[case] full size {name}: B={w.B} H={w.H} L={w.L} d={w.d_k} r={w.r} C={w.chunk}, heads {sample}", flush=True)
+    dev = torch.device("cuda:0")
+    B, H, L, r, d = w.B, w.H, w.L, w.r, w.d_k
+    bf = torch.bfloat16
+    Q = torch.empty((B * H, L, d), dtype=bf, device=dev)
+    K = torch.empty((B * H, L, r, d), dtype=bf, device=dev)
+    V = torch.empty((B * H, L, r, d), dtype=bf, device=dev)
+    beta = torch.empty((B * H, L, r), dtype=bf, device=dev)
+    S0 = torch.empty((B * H, d, d), dtype=torch.float32, device=dev) if w.s0_std > 0 else None
+    kept = {}
+    for h in range(B * H):
+        q, k, v, b, s0 = synth.head_inputs(w, h)
+        Q[h], K[h], V[h], beta[h] = (torch.from_numpy(a).to(dev).to(bf) for a in (q, k, v, b))
+        if S0 is not None:
+            S0[h] = torch.from_numpy(s0).to(dev)
+        if h in sample:
+            kept[h] = (q, k, v, b, s0)
+    shp = lambda t: t.reshape((B, H) + tuple(t.shape[1:]))
+    O, SL = pf.delta_fwd(shp(Q), shp(K), shp(V), shp(beta), None if S0 is None else shp(S0), chunk=w.chunk)
+    torch.cuda.synchronize()
+    assert pf.pf_delta_fwd_supported(d, d, r, w.chunk, pf.PF_BF16) == 2
+    O = O.reshape(B * H, L, d)
+    SL = SL.reshape(B * H, d, d)
+    assert bool(torch.isfinite(O).all()) and bool(torch.isfinite(SL).all())
+    for h in sample:
+        q, k, v, b, s0 = kept[h]
+        Oref, SLref = oracle.delta_fwd(q[None], k[None], v[None], b[None], None if s0 is None else s0[None])
+        eO = rel_l2(O[h].float().cpu().numpy(), Oref[0])
+        eS = rel_l2(SL[h].cpu().numpy(), SLref[0])
+        print(f"        head {h}: relL2(O)={eO:.3e} relL2(S_L)={eS:.3e} |S_L|={np.linalg.norm(SLref):.2f}", flush=True)
+        assert eO <= 2e-2 and eS <= 2e-2
