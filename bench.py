@@ -131,17 +131,17 @@ def main():
         n = C * r
         NC = L // C
         mk = lambda m: torch.empty((B, H, NC, m), dtype=torch.bfloat16, device=dev)
-        Wt, Ut, Kt, Pt, Qt = mk(n * dk), mk(n * dv), mk(n * dk), mk(C * n), mk(C * dk)
+        Tt, Pt = mk(n * n), mk(C * n)
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
         for i in range(args.warmup + args.steps):
             j = i - args.warmup
             if j >= 0:
                 ev[j][0].record(stream)
-            st = pf.pf_delta_chunk_flow(Q, K, V, beta, Wt, Ut, Kt, Pt, Qt, B, H, L, dk, dv, r, C, stream)
+            st = pf.pf_delta_chunk_flow(Q, K, beta, Tt, Pt, B, H, L, dk, dv, r, C, stream)
             assert st == pf.PF_OK, st
             if j >= 0:
                 ev[j][1].record(stream)
-            st = pf.pf_delta_chunk_scan(Wt, Ut, Kt, Pt, Qt, S0, O, SL, B, H, L, dk, dv, r, C, stream)
+            st = pf.pf_delta_chunk_scan(Q, K, V, beta, Tt, Pt, S0, O, SL, B, H, L, dk, dv, r, C, stream)
             assert st == pf.PF_OK, st
             if j >= 0:
                 ev[j][2].record(stream)

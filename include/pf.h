@@ -11,9 +11,10 @@
  * Section 3.1 (A = beta k, Atil = -beta v, B = -k; rank r = one additive rank-r increment
  * per token), with the "memory readout" of Section 1.1 on the updated state.  For r = 1 this
  * is the DeltaNet update of Section 1.3.  It is computed chunk by chunk as the flow of the
- * system (Section 3): per chunk the compact form W, U of Theorem 3.2, obtained by the block
- * forward substitution of Proposition 3.3; the readout inside the chunk from the same W, U;
- * and a state hand-over from chunk to chunk.
+ * system (Section 3): per chunk the compact form of Theorem 3.2 (W = T beta K, U = -T beta V with
+ * T the inverse of the chunk's triangular system matrix, obtained by the block substitution
+ * of Proposition 3.3); the readout inside the chunk from the same T; and a state hand-over from
+ * chunk to chunk.
  *
  * Conventions common to every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never
@@ -107,44 +108,37 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
  *
  *   Cmat = Id + M (.) diag(beta) K K^T,  M[(t,i),(s,j)] = 1 iff s < t     (Theorem 3.2 in delta
  *          variables; Id - M (.) A B^T of the theorem)
- *   W    = Cmat^{-1} (beta (.) K)     [n, d]      W of Theorem 3.2
- *   U'   = Cmat^{-1} (beta (.) V)     [n, d]      -U of Theorem 3.2
+ *   T    = Cmat^{-1}                  [n, n]      lower block-triangular; W = T (beta (.) K) and
+ *                                                 -U = T (beta (.) V) are W and U of Theorem 3.2
  *   P    = Mbar (.) Q K^T             [chunk, n]  Mbar[t,(s,j)] = 1 iff s <= t (readout mask)
  *
- * The five outputs hold -W, U', K, P and Q of each chunk, bf16, chunk after chunk in (b, h, c)
- * order, each chunk stored as a sequence of 16-row MFMA operand tiles: 64 "lanes" x 8 (or 4)
- * consecutive elements per tile, lane = 16 g + r16.  With MT = n/16, NKT = n/32, DT = d/16,
- * NKS = d/32, CT = chunk/16:
+ * Both outputs are bf16, chunk after chunk in (b, h, c) order, each chunk stored as a sequence
+ * of 16-row MFMA operand tiles of 64 "lanes" x 8 elements, lane = 16 g + r16.  With MT = n/16,
+ * NKT = n/32, CT = chunk/16 and kk(g, e) = 4 g + e (e < 4), 16 + 4 g + e - 4 (e >= 4):
  *
- *   Wt [B,H,NC][MT][NKS][64][8]   -W[16 mt + r16][32 ks + 8 g + e]
- *   Ut [B,H,NC][MT][DT ][64][4]   U'[16 mt + 4 g + e][16 dt + r16]
- *   Kt [B,H,NC][DT][NKT][64][8]   K[32 kt + 8 g + e][16 a + r16]
- *   Pt [B,H,NC][CT][NKT][64][8]   P[16 tt + r16][32 kt + 4 g + e]           for e < 4,
- *                                 P[16 tt + r16][32 kt + 16 + 4 g + (e - 4)] for e >= 4;
- *                                 tiles with 32 kt >= r (16 tt + 16) lie wholly behind the mask
- *                                 and are left unwritten
- *   Qt [B,H,NC][CT][NKS][64][8]   Q[16 tt + r16][32 ks + 8 g + e]
+ *   Tt [B,H,NC][MT][NKT][64][8]   T[16 mt + r16][32 kt + kk(g, e)]   written only for 2 kt <= mt
+ *   Pt [B,H,NC][CT][NKT][64][8]   P[16 tt + r16][32 kt + kk(g, e)]   written only for
+ *                                                                    32 kt < r (16 tt + 16)
  *
- * Element counts per (b, h): Wt, Ut, Kt: L*r*d; Pt: L*n; Qt: L*d.  Inputs as in pf_delta_fwd.
- * All five outputs are required.
+ * (tiles outside those ranges are identically zero; they are never read by pf_delta_chunk_scan).
+ * Element counts per (b, h): Tt: NC*n*n, Pt: L*n.  Q, K, beta as in pf_delta_fwd.
  */
-pf_status pf_delta_chunk_flow(const void *Q, const void *K, const void *V, const void *beta,
-                              void *Wt, void *Ut, void *Kt, void *Pt, void *Qt,
+pf_status pf_delta_chunk_flow(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,
                               int B, int H, int L, int d_k, int d_v, int r, int chunk,
                               pf_stream stream);
 
 /*
  * Step 3 of Section 3 fused with the readout, MFMA path only: hands the state from chunk to
- * chunk and reads out inside each chunk, from the arrays pf_delta_chunk_flow wrote:
+ * chunk and reads out inside each chunk, from the inputs and the arrays pf_delta_chunk_flow wrote:
  *
- *   U_eff = U' - W S_c^T          (U + W S_0^T of Theorem 3.2, up to the sign convention)
- *   O_c   = Q S_c^T + P U_eff      (discrete flow of Section 3.1 truncated at each token)
- *   S_c+1 = S_c + U_eff^T K        (S_1 of Theorem 3.2)
+ *   U_eff = T (beta (.) (V - K S_c^T))   (= U' - W S_c^T: U + W S_0^T of Theorem 3.2, sign folded)
+ *   O_c   = Q S_c^T + P U_eff             (discrete flow of Section 3.1 truncated at each token)
+ *   S_c+1 = S_c + U_eff^T K               (S_1 of Theorem 3.2)
  *
- * S0, O, S_L as in pf_delta_fwd (dt = PF_BF16).
+ * Q, K, V, beta, S0, O, S_L as in pf_delta_fwd (dt = PF_BF16).
  */
-pf_status pf_delta_chunk_scan(const void *Wt, const void *Ut, const void *Kt, const void *Pt,
-                              const void *Qt, const float *S0, void *O, float *S_L,
+pf_status pf_delta_chunk_scan(const void *Q, const void *K, const void *V, const void *beta,
+                              const void *Tt, const void *Pt, const float *S0, void *O, float *S_L,
                               int B, int H, int L, int d_k, int d_v, int r, int chunk,
                               pf_stream stream);
 

@@ -40,9 +40,9 @@ def _load() -> ctypes.CDLL:
     lib.pf_delta_fwd.restype = i
     lib.pf_delta_fwd.argtypes = [vp] * 7 + [i] * 8 + [vp, sz, vp]
     lib.pf_delta_chunk_flow.restype = i
-    lib.pf_delta_chunk_flow.argtypes = [vp] * 9 + [i] * 7 + [vp]
+    lib.pf_delta_chunk_flow.argtypes = [vp] * 5 + [i] * 7 + [vp]
     lib.pf_delta_chunk_scan.restype = i
-    lib.pf_delta_chunk_scan.argtypes = [vp] * 8 + [i] * 7 + [vp]
+    lib.pf_delta_chunk_scan.argtypes = [vp] * 9 + [i] * 7 + [vp]
     return lib
 
 
@@ -91,14 +91,13 @@ def pf_delta_fwd(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, wor
                                  _stream_handle(stream)))
 
 
-def pf_delta_chunk_flow(Q, K, V, beta, Wt, Ut, Kt, Pt, Qt, B, H, L, d_k, d_v, r, chunk, stream=None) -> int:
-    return int(_lib.pf_delta_chunk_flow(_ptr(Q), _ptr(K), _ptr(V), _ptr(beta), _ptr(Wt), _ptr(Ut),
-                                        _ptr(Kt), _ptr(Pt), _ptr(Qt), B, H, L, d_k, d_v, r, chunk,
-                                        _stream_handle(stream)))
+def pf_delta_chunk_flow(Q, K, beta, Tt, Pt, B, H, L, d_k, d_v, r, chunk, stream=None) -> int:
+    return int(_lib.pf_delta_chunk_flow(_ptr(Q), _ptr(K), _ptr(beta), _ptr(Tt), _ptr(Pt),
+                                        B, H, L, d_k, d_v, r, chunk, _stream_handle(stream)))
 
 
-def pf_delta_chunk_scan(Wt, Ut, Kt, Pt, Qt, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, stream=None) -> int:
-    return int(_lib.pf_delta_chunk_scan(_ptr(Wt), _ptr(Ut), _ptr(Kt), _ptr(Pt), _ptr(Qt), _ptr(S0),
+def pf_delta_chunk_scan(Q, K, V, beta, Tt, Pt, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, stream=None) -> int:
+    return int(_lib.pf_delta_chunk_scan(_ptr(Q), _ptr(K), _ptr(V), _ptr(beta), _ptr(Tt), _ptr(Pt), _ptr(S0),
                                         _ptr(O), _ptr(S_L), B, H, L, d_k, d_v, r, chunk,
                                         _stream_handle(stream)))
 

@@ -8,24 +8,21 @@ constexpr size_t kAlign = 256;
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Offsets (bytes) of the five per-chunk arrays inside the MFMA path's workspace.
+// Offsets (bytes) of the two per-chunk arrays inside the MFMA path's workspace.
 struct WorkspacePlan {
-    size_t oW, oU, oK, oP, oQ, total;
+    size_t oT, oP, total;
 };
 WorkspacePlan plan_workspace(int heads, int L, int d, int r, int chunk)
 {
+    (void)d;
     const size_t n = (size_t)chunk * r;
     const size_t tok = (size_t)heads * L;          // tokens over all heads
-    const size_t wk = tok * r * d * 2;             // Wt, Ut, Kt: bf16, L*r*d per head
-    const size_t pb = tok * n * 2;                 // Pt: bf16, L*n per head
-    const size_t qb = tok * d * 2;                 // Qt: bf16, L*d per head
+    const size_t tb = tok / chunk * n * n * 2;     // Tt: bf16, n*n per chunk
+    const size_t pb = tok * n * 2;                 // Pt: bf16, chunk*n per chunk
     WorkspacePlan p;
     size_t o = 0;
-    p.oW = o; o = round_up(o + wk, kAlign);
-    p.oU = o; o = round_up(o + wk, kAlign);
-    p.oK = o; o = round_up(o + wk, kAlign);
+    p.oT = o; o = round_up(o + tb, kAlign);
     p.oP = o; o = round_up(o + pb, kAlign);
-    p.oQ = o; o = round_up(o + qb, kAlign);
     p.total = o;
     return p;
 }
@@ -108,45 +105,41 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
     if (!workspace || workspace_bytes < wp.total) return PF_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PF_ERR_ALIGN;
     char *ws = static_cast<char *>(workspace);
-    hipError_t e = pf::launch_chunk_flow(Q, K, V, beta, ws + wp.oW, ws + wp.oU, ws + wp.oK, ws + wp.oP,
-                                         ws + wp.oQ, heads, L, d_k, r, chunk, s);
+    hipError_t e = pf::launch_chunk_flow(Q, K, beta, ws + wp.oT, ws + wp.oP, heads, L, d_k, r, chunk, s);
     if (e != hipSuccess) return PF_ERR_LAUNCH;
-    e = pf::launch_chunk_scan(ws + wp.oW, ws + wp.oU, ws + wp.oK, ws + wp.oP, ws + wp.oQ, S0, O, S_L,
-                              heads, L, d_k, r, chunk, s);
+    e = pf::launch_chunk_scan(Q, K, V, beta, ws + wp.oT, ws + wp.oP, S0, O, S_L, heads, L, d_k, r, chunk, s);
     return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
 }
 
-pf_status pf_delta_chunk_flow(const void *Q, const void *K, const void *V, const void *beta, void *Wt,
-                              void *Ut, void *Kt, void *Pt, void *Qt, int B, int H, int L, int d_k, int d_v,
-                              int r, int chunk, pf_stream stream)
+pf_status pf_delta_chunk_flow(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,
+                              int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_stream stream)
 {
-    if (!Q || !K || !V || !beta || !Wt || !Ut || !Kt || !Pt || !Qt) return PF_ERR_NULL;
+    if (!Q || !K || !beta || !Tt || !Pt) return PF_ERR_NULL;
     pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
     if (st != PF_OK) return st;
     if (family(d_k, d_v, r, chunk, PF_BF16) != 2) return PF_ERR_UNSUPPORTED;
     if (L % chunk != 0) return PF_ERR_SHAPE;
-    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(beta) || !aligned16(Wt) ||
-        !aligned16(Ut) || !aligned16(Kt) || !aligned16(Pt) || !aligned16(Qt))
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(beta) || !aligned16(Tt) || !aligned16(Pt))
         return PF_ERR_ALIGN;
     if (L == 0) return PF_OK;
-    hipError_t e = pf::launch_chunk_flow(Q, K, V, beta, Wt, Ut, Kt, Pt, Qt, B * H, L, d_k, r, chunk,
+    hipError_t e = pf::launch_chunk_flow(Q, K, beta, Tt, Pt, B * H, L, d_k, r, chunk,
                                          static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
 }
 
-pf_status pf_delta_chunk_scan(const void *Wt, const void *Ut, const void *Kt, const void *Pt,
-                              const void *Qt, const float *S0, void *O, float *S_L, int B, int H, int L,
+pf_status pf_delta_chunk_scan(const void *Q, const void *K, const void *V, const void *beta, const void *Tt,
+                              const void *Pt, const float *S0, void *O, float *S_L, int B, int H, int L,
                               int d_k, int d_v, int r, int chunk, pf_stream stream)
 {
-    if (!Wt || !Ut || !Kt || !Pt || !Qt || !O) return PF_ERR_NULL;
+    if (!Q || !K || !V || !beta || !Tt || !Pt || !O) return PF_ERR_NULL;
     pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
     if (st != PF_OK) return st;
     if (family(d_k, d_v, r, chunk, PF_BF16) != 2) return PF_ERR_UNSUPPORTED;
     if (L % chunk != 0) return PF_ERR_SHAPE;
-    if (!aligned16(Wt) || !aligned16(Ut) || !aligned16(Kt) || !aligned16(Pt) || !aligned16(Qt) ||
-        !aligned16(S0) || !aligned16(O) || !aligned16(S_L))
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(beta) || !aligned16(Tt) ||
+        !aligned16(Pt) || !aligned16(S0) || !aligned16(O) || !aligned16(S_L))
         return PF_ERR_ALIGN;
-    hipError_t e = pf::launch_chunk_scan(Wt, Ut, Kt, Pt, Qt, S0, O, S_L, B * H, L, d_k, r, chunk,
+    hipError_t e = pf::launch_chunk_scan(Q, K, V, beta, Tt, Pt, S0, O, S_L, B * H, L, d_k, r, chunk,
                                          static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
 }

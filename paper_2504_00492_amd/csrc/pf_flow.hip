@@ -1,29 +1,34 @@
 // Chunk-flow kernel: step 2 of Section 3 of ParallelFlow (arXiv 2504.00492), "parallel
-// compute".  One workgroup (8 wavefronts) per (b, h, chunk); no dependence between chunks.
+// compute".  Persistent workgroups (8 wavefronts) walk the (b, h, chunk) triples; chunks do not
+// depend on each other.
 //
 // In delta variables (Remark in Section 3.1: A = beta k, Atil = -beta v, B = -k) Theorem 3.2
 // reads, with n = chunk * r virtual tokens and M strict in time,
-//     (Id + G) W = beta (.) K,   (Id + G) U' = beta (.) V,   G = M (.) diag(beta) K K^T,
-// where U' = -U.  The system is solved by block forward substitution (Proposition 3.3) on
-// 32-row blocks, directly for the right-hand sides (the n x n inverse is never formed):
-//     X_i = T_ii ( beta_i (.) [K_i | V_i]  -  sum_{j<i} G_ij X_j ),    T_ii = (Id + G_ii)^{-1}.
-// T_ii (32 x 32) comes from two 16 x 16 forward substitutions in fp32 on the vector ALU and
-// one block merge  T_21 = -T_22 G_21 T_11  on MFMA.
+//     W = T (beta (.) K),   U' = T (beta (.) V),   T = (Id + G)^{-1},   G = M (.) diag(beta) K K^T,
+// where U' = -U.  What the state hand-over needs of the chunk is U' - W S^T = T (beta (.) (V - K S^T)),
+// so T itself is the compact form that is handed on: n x n lower block-triangular, which is
+// smaller than W and U' together, and it depends on K and beta only.
 //
-// Work split.  The 2 d right-hand-side columns are dealt to the 8 wavefronts (waves 0-3 the
-// key columns, waves 4-7 the value columns).  A wave keeps every finished X_j of its column
-// slice in registers, already in MFMA B-operand form, so the substitution itself needs no
-// LDS traffic for X.  G_ij and T_ii are built cooperatively and read by all waves as A
-// operands from LDS.  Gram blocks are computed transposed so that an accumulator tile (4
-// consecutive j per lane) goes to row-major LDS with 8-byte writes.
+// T is obtained by the block substitution of Proposition 3.3 on 32-row blocks, run on the
+// transposed system  (Id + G)^T X = Id  (X = T^T, upper block-triangular, solved from the last
+// block up):
+//     X_j = T_jj^T ( E_j  -  sum_{i > j} G_ij^T X_i ).
+// Solving for T^T rather than T is a layout choice: an MFMA accumulator tile of X (4 consecutive
+// rows of T^T per lane) is 4 consecutive columns of one row of T, which is the A-operand form
+// the scan kernel wants, so finished tiles go from registers straight to their place in the
+// hand-over array.  T_jj (32 x 32) comes from two 16 x 16 forward substitutions in fp32 on the
+// vector ALU and one block merge T_21 = -T_22 G_21 T_11 on MFMA.
 //
-// The kernel is persistent: a workgroup walks chunks blockIdx.x, blockIdx.x + gridDim.x, ...
-// and, while it works on one chunk, the K, V, beta and Q of its next chunk are already on
-// their way from HBM into registers (each register set is refilled right after its last use),
-// so that loads and MFMA work of neighbouring chunks overlap on a CU that, because of the LDS
-// footprint, holds a single workgroup.
+// Work split.  The n columns of X (= rows of T) are dealt to the waves in 16-column slices; a
+// wave keeps the finished blocks X_i of its slices in registers, already in B-operand form (see
+// pf_common.cuh), so the substitution needs no LDS traffic for X.  G^T block-columns and T_jj^T
+// are built cooperatively and read by all waves as A operands from LDS.  P = Mbar (.) Q K^T
+// (readout mask, inclusive in time) is computed from the same resident K.
 //
-// Outputs: the tiled operand arrays described in pf_layout.h.
+// While a chunk is processed, K, beta and Q of the workgroup's next chunk are already on their
+// way from HBM into registers.
+//
+// Outputs: the tiled operand arrays Tt and Pt described in pf_layout.h.
 #include "pf_internal.h"
 #include "pf_common.cuh"
 #include "pf_layout.h"
@@ -36,70 +41,57 @@ constexpr int kFlowWaves = kFlowThreads / 64;
 template <int D, int N, int C>
 struct FlowLds {
     static constexpr int NB = N / 32;       // 32-row blocks per chunk
-    static constexpr int KP = D + 8;        // pitch of K / V / Q rows (bf16)
-    static constexpr int GP = N + 8;        // pitch of a G block-row (bf16)
-    static constexpr int TP = 40;           // pitch of a T_ii row (bf16)
-    static constexpr int NP = 36;           // pitch of the fp32 scratch used to build T_ii
-    static constexpr int FW = D / 4;        // right-hand-side columns per wave
-    static constexpr int WP = FW + 8;       // pitch of the per-wave W staging tile (bf16)
+    static constexpr int KP = D + 8;        // pitch of K / Q rows (bf16)
+    static constexpr int GP = N + 8;        // pitch of a row of a G^T block-column (bf16)
+    static constexpr int TP = 40;           // pitch of a T_jj^T row (bf16)
+    static constexpr int NP = 36;           // pitch of the fp32 scratch used to build T_jj
     static constexpr size_t oKs = 0;
     static constexpr size_t oBs = oKs + (size_t)N * KP * 2;
     static constexpr size_t oTs = oBs + (size_t)N * 4;
     static constexpr size_t oUn = oTs + (size_t)NB * 32 * TP * 2;       // region reused by phase
-    // phase "build T": fp32 scratch, one 32 x NP tile per wave that has a diagonal block
+    // phase "build T_jj": fp32 scratch, one 32 x NP tile per wave that has a diagonal block
     static constexpr size_t szNs = (size_t)(NB < kFlowWaves ? NB : kFlowWaves) * 32 * NP * 4;
-    // phase "substitute": G block-row (x2), W staging (4 waves), V block (x2).  The V buffers
-    // lie behind the scratch tiles because V block 0 is staged before T is built.
-    static constexpr size_t oGs = oUn;
-    static constexpr size_t oWs = oGs + (size_t)2 * 32 * GP * 2;
-    static constexpr size_t oVs = oWs + (size_t)4 * 32 * WP * 2;
-    static_assert(oVs - oUn >= szNs, "V buffers must not overlap the scratch tiles");
-    static constexpr size_t szS = oVs + (size_t)2 * 32 * KP * 2 - oUn;
+    // phase "substitute": G^T block-column (x2)
+    static constexpr size_t szG = (size_t)2 * 32 * GP * 2;
     // phase "P": the chunk's queries
     static constexpr size_t szQ = (size_t)C * KP * 2;
-    static constexpr size_t szUn = szNs > szS ? (szNs > szQ ? szNs : szQ) : (szS > szQ ? szS : szQ);
+    static constexpr size_t szUn = szNs > szG ? (szNs > szQ ? szNs : szQ) : (szG > szQ ? szG : szQ);
     static constexpr size_t total = oUn + szUn;
 };
 
 template <int D, int N, int C>
 __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
-    const bf16 *__restrict__ Q, const bf16 *__restrict__ K, const bf16 *__restrict__ V,
-    const bf16 *__restrict__ beta, bf16 *__restrict__ Wt, bf16 *__restrict__ Ut, bf16 *__restrict__ Kt,
-    bf16 *__restrict__ Pt, bf16 *__restrict__ Qt, int nchunks)
+    const bf16 *__restrict__ Q, const bf16 *__restrict__ K, const bf16 *__restrict__ beta,
+    bf16 *__restrict__ Tt, bf16 *__restrict__ Pt, int nchunks)
 {
     using Ld = FlowLds<D, N, C>;
     constexpr int R = N / C;          // rank: virtual tokens per token
     constexpr int NB = Ld::NB;
-    constexpr int FW = Ld::FW;
-    constexpr int NT = FW / 16;       // 16-column tiles of the right-hand side per wave
-    constexpr int NKS = D / 32, NKT = N / 32, DT = D / 16, CT = C / 16;
-    constexpr int KP = Ld::KP, GP = Ld::GP, TP = Ld::TP, NP = Ld::NP, WP = Ld::WP;
+    constexpr int NKS = D / 32, NKT = N / 32, CT = C / 16;
+    constexpr int KP = Ld::KP, GP = Ld::GP, TP = Ld::TP, NP = Ld::NP;
     constexpr int NTHR = kFlowThreads;
-    static_assert(32 % R == 0 && N % 32 == 0 && C % 16 == 0 && D % 64 == 0, "tile shapes");
+    constexpr int NS = N / 16;                                          // 16-column slices of X
+    constexpr int SPW = (NS + kFlowWaves - 1) / kFlowWaves;             // slices per wave
+    static_assert(32 % R == 0 && N % 32 == 0 && C % 16 == 0 && D % 32 == 0, "tile shapes");
+    static_assert(SPW <= 2, "a wave owns at most two slices");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16 *Ks = reinterpret_cast<bf16 *>(smem + Ld::oKs);
     float *bs = reinterpret_cast<float *>(smem + Ld::oBs);
     bf16 *Ts = reinterpret_cast<bf16 *>(smem + Ld::oTs);
     float *NsAll = reinterpret_cast<float *>(smem + Ld::oUn);
-    bf16 *Vs = reinterpret_cast<bf16 *>(smem + Ld::oVs);
-    bf16 *Gs = reinterpret_cast<bf16 *>(smem + Ld::oGs);
-    bf16 *WsAll = reinterpret_cast<bf16 *>(smem + Ld::oWs);
+    bf16 *Gs = reinterpret_cast<bf16 *>(smem + Ld::oUn);
     bf16 *Qs = reinterpret_cast<bf16 *>(smem + Ld::oUn);
 
     const int tid0 = threadIdx.x;
 
     // ---- register sets that carry the next chunk's inputs
     constexpr int VPR = D / 8;                         // 16-byte vectors per row
-    constexpr int KV = (N * D / 8 + NTHR - 1) / NTHR;  // vectors of K (and of V) per thread
+    constexpr int KV = (N * D / 8 + NTHR - 1) / NTHR;  // vectors of K per thread
     constexpr int QV = (C * D / 8 + NTHR - 1) / NTHR;  // vectors of Q per thread
-    constexpr int VVEC = 32 * VPR;                     // vectors in one 32-row block
-    constexpr int BPP = NTHR / VVEC;                   // 32-row blocks covered by one pass of the workgroup
-    static_assert(VVEC <= NTHR && NTHR % VVEC == 0, "a pass covers whole blocks");
-    constexpr int VR = KV > 4 ? 4 : KV;                // V travels through a ring of VR passes
-    static_assert(KV % VR == 0, "ring slots are reused with a fixed stride");
-    bf16x8 kreg[KV], vreg[VR], qreg[QV];
+    bf16x8 kreg[KV], qreg[QV];
     bf16 breg = (bf16)0.0f;   // kept as loaded: converting here would wait for the fetch
+    static_assert(N <= NTHR, "beta of a chunk is fetched by one pass");
 
     auto fetch_k = [&](size_t c) {
         const bf16 *Kg = K + c * (size_t)N * D;
@@ -110,10 +102,6 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
         }
         breg = beta[c * (size_t)N + (tid0 % N)];   // every thread loads: no branch, always in range
     };
-    auto fetch_v_pass = [&](size_t c, int q) {       // the blocks [q BPP, (q+1) BPP) of V
-        const int v = tid0 + NTHR * q;
-        if ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8) vreg[q % VR] = ld8(V + c * (size_t)N * D + (size_t)v * 8);
-    };
     auto fetch_q = [&](size_t c) {
         const bf16 *Qg = Q + c * (size_t)C * D;
 #pragma unroll
@@ -122,13 +110,10 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
             if ((q + 1) * NTHR <= C * D / 8 || v < C * D / 8) qreg[q] = ld8(Qg + (size_t)v * 8);
         }
     };
-    static_assert(N <= NTHR, "beta of a chunk is fetched by one pass");
 
     size_t cid = blockIdx.x;
     if (cid < (size_t)nchunks) {
         fetch_k(cid);
-#pragma unroll
-        for (int q = 0; q < VR; ++q) fetch_v_pass(cid, q);
         fetch_q(cid);
     }
 
@@ -140,16 +125,11 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
         asm volatile("" : "+v"(tid));
         const int w = tid >> 6, lane = tid & 63;
         const int r16 = lane & 15, g = lane >> 4;
-        const bool isV = w >= 4;               // waves 4-7 solve for U', waves 0-3 for W
-        const int cb = (w & 3) * FW;           // first column of this wave's slice inside K or V
-
-        const size_t nxt = cid + gridDim.x;
-        const bool more = nxt < (size_t)nchunks;
-        bf16 *Wg = Wt + cid * (size_t)N * D;
-        bf16 *Ug = Ut + cid * (size_t)N * D;
-        bf16 *Ktg = Kt + cid * (size_t)N * D;
+        // The fetch for "the next chunk" is unconditional (the last chunk re-fetches itself): a
+        // branch around a load makes every later wait assume the shorter queue.
+        const size_t nxt = cid + gridDim.x < (size_t)nchunks ? cid + gridDim.x : cid;
+        bf16 *Ttg = Tt + cid * (size_t)N * N;
         bf16 *Ptg = Pt + cid * (size_t)C * N;
-        bf16 *Qtg = Qt + cid * (size_t)C * D;
 
         // ------------------------------------------------------------ K, beta: registers -> LDS
 #pragma unroll
@@ -158,30 +138,10 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
             if ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8) st8(&Ks[(v / VPR) * KP + (v % VPR) * 8], kreg[q]);
         }
         if (tid < N) bs[tid] = (float)breg;
-        // V block b: registers -> LDS buffer (b & 1).  When that frees a ring slot, the slot is
-        // refilled with the pass VR further down the stream (this chunk's, then the next one's).
-        auto stage_v = [&](int b) {
-            const int q = b / BPP;
-            if (tid / VVEC == b % BPP)
-                st8(&Vs[(b & 1) * 32 * KP + ((tid % VVEC) / VPR) * KP + (tid % VPR) * 8], vreg[q % VR]);
-            if (b % BPP == BPP - 1 || b == NB - 1) {
-                if (q + VR < KV) fetch_v_pass(cid, q + VR);
-                else if (more) fetch_v_pass(nxt, q + VR - KV);
-            }
-        };
-        stage_v(0);
         __syncthreads();
-        if (more) fetch_k(nxt);
+        fetch_k(nxt);
 
-        // ------------------------------------------------------------ K^T tiles out
-        for (int it = w; it < DT * NKT; it += kFlowWaves) {
-            const int a = it / NKT, kt = it % NKT;
-            const bf16 *p = &Ks[(32 * kt + 8 * g + (r16 >> 2)) * KP + 16 * a + 4 * (r16 & 3)];
-            bf16x4 lo = lds_read_tr4(p), hi = lds_read_tr4(p + 4 * KP);
-            st8(Ktg + ((size_t)(a * NKT + kt) * 64 + lane) * 8, join(lo, hi));
-        }
-
-        // ------------------------------------------------------------ T_ii for every 32-block
+        // ------------------------------------------------------------ T_jj^T for every 32-block
         // Each wave builds whole diagonal blocks on its own (private scratch tile, private
         // destination), so the steps below are ordered by program order within the wave.
         {
@@ -255,12 +215,13 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
                 }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 {
+                    // store the block transposed: row of the stored tile = column of T_jj
                     const int row = lane >> 1, half = lane & 1;
                     bf16x8 lo, hi;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        lo[e] = (bf16)Ns[row * NP + 16 * half + e];
-                        hi[e] = (bf16)Ns[row * NP + 16 * half + 8 + e];
+                        lo[e] = (bf16)Ns[(16 * half + e) * NP + row];
+                        hi[e] = (bf16)Ns[(16 * half + 8 + e) * NP + row];
                     }
                     st8(&Ts[(db * 32 + row) * TP + 16 * half], lo);
                     st8(&Ts[(db * 32 + row) * TP + 16 * half + 8], hi);
@@ -270,135 +231,108 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
         }
         __syncthreads();   // T blocks visible to everyone; scratch region free for the next phase
 
-        // ------------------------------------------------------------ block forward substitution
-        bf16x8 X[NB][NT];                      // finished blocks of this wave's slice, B-operand form
+        // ------------------------------------------------------------ block substitution, last block first
+        // Slice ownership: wave w has slice w and (when there are 16 slices) slice 15 - w, which
+        // evens out the triangular amount of work.
+        bf16x8 X[SPW][NB];   // finished blocks of this wave's slices, B-operand form
 
-        // -G_ij for every j < i, transposed product so that lanes hold 4 consecutive j.
-        auto gram_row = [&](int i, int buf) {
+        // -G^T block-column j: rows b = the 32 tokens of block j, columns a = every later token.
+        // Product taken as (rows a) x (cols b) so that lanes hold 4 consecutive a.
+        auto gram_col = [&](int j, int buf) {
             bf16 *Gb = Gs + buf * 32 * GP;
             const int nh = w & 1;
             bf16x8 bk[NKS];
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) bk[ks] = ld8(&Ks[(32 * i + 16 * nh + r16) * KP + 32 * ks + 8 * g]);
-            const float nbeta = -bs[32 * i + 16 * nh + r16];
-            for (int jt = (w >> 1); jt < 2 * i; jt += 8) {
-                const bool two = jt + 4 < 2 * i;       // second tile of the pair exists
-                const int jt2 = two ? jt + 4 : jt;
+            for (int ks = 0; ks < NKS; ++ks) bk[ks] = ld8(&Ks[(32 * j + 16 * nh + r16) * KP + 32 * ks + 8 * g]);
+            for (int at = 2 * (j + 1) + (w >> 1); at < 2 * NB; at += 8) {
+                const bool two = at + 4 < 2 * NB;       // second tile of the pair exists
+                const int at2 = two ? at + 4 : at;
                 f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < NKS; ++ks) {
-                    acc0 = mfma16(ld8(&Ks[(16 * jt + r16) * KP + 32 * ks + 8 * g]), bk[ks], acc0);
-                    acc1 = mfma16(ld8(&Ks[(16 * jt2 + r16) * KP + 32 * ks + 8 * g]), bk[ks], acc1);
+                    acc0 = mfma16(ld8(&Ks[(16 * at + r16) * KP + 32 * ks + 8 * g]), bk[ks], acc0);
+                    acc1 = mfma16(ld8(&Ks[(16 * at2 + r16) * KP + 32 * ks + 8 * g]), bk[ks], acc1);
                 }
-                st4(&Gb[(16 * nh + r16) * GP + 16 * jt + 4 * g], cvt4(acc0 * nbeta));
-                if (two) st4(&Gb[(16 * nh + r16) * GP + 16 * jt2 + 4 * g], cvt4(acc1 * nbeta));
+                f32x4 nb0, nb1;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    nb0[e] = -bs[16 * at + 4 * g + e];
+                    nb1[e] = -bs[16 * at2 + 4 * g + e];
+                }
+                st4(&Gb[(16 * nh + r16) * GP + 16 * at + 4 * g], cvt4(acc0 * nb0));
+                if (two) st4(&Gb[(16 * nh + r16) * GP + 16 * at2 + 4 * g], cvt4(acc1 * nb1));
             }
         };
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const int buf = i & 1;
-            if (i + 1 < NB) {
-                gram_row(i + 1, buf ^ 1);
-                stage_v(i + 1);
-            }
 
-            const bf16 *src = isV ? (Vs + buf * 32 * KP) : (Ks + 32 * i * KP);
+        // Block j reads column j of G^T from buffer j & 1.  The last block has no later block and
+        // needs none; column NB - 2 is built here, and every later step builds the column of the
+        // step after it into the other buffer.
+        if (NB > 1) gram_col(NB - 2, (NB - 2) & 1);
+        __syncthreads();
+#pragma unroll
+        for (int step = 0; step < NB; ++step) {
+            const int j = NB - 1 - step;
+            const int buf = j & 1;
+            if (step > 0 && j > 0) gram_col(j - 1, (j - 1) & 1);
             const bf16 *Gb = Gs + buf * 32 * GP;
-            f32x4 acc[2][NT];
-            // right-hand side beta_i (.) [K_i | V_i], read transposed into accumulator layout
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi) {
-                f32x4 bt;
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) bt[jj] = bs[32 * i + 16 * mi + 4 * g + jj];
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    bf16x4 v = lds_read_tr4(&src[(16 * mi + 4 * g + (r16 >> 2)) * KP + cb + 16 * nt + 4 * (r16 & 3)]);
-                    acc[mi][nt] = __builtin_convertvector(v, f32x4) * bt;
-                }
-            }
-            // minus sum_j G_ij X_j  (G stored negated)
-#pragma unroll
-            for (int j = 0; j < i; ++j) {
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi) {
-                    bf16x8 a = join(ld4(&Gb[(16 * mi + r16) * GP + 32 * j + 4 * g]),
-                                    ld4(&Gb[(16 * mi + r16) * GP + 32 * j + 16 + 4 * g]));
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) acc[mi][nt] = mfma16(a, X[j][nt], acc[mi][nt]);
-                }
-            }
-            // X_i = T_ii R_i
-            f32x4 xacc[2][NT];
-            {
-                bf16x8 rb[NT];
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) rb[nt] = join(cvt4(acc[0][nt]), cvt4(acc[1][nt]));
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi) {
-                    bf16x8 a = join(ld4(&Ts[(i * 32 + 16 * mi + r16) * TP + 4 * g]),
-                                    ld4(&Ts[(i * 32 + 16 * mi + r16) * TP + 16 + 4 * g]));
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) {
-                        f32x4 z = {0.f, 0.f, 0.f, 0.f};
-                        xacc[mi][nt] = mfma16(a, rb[nt], z);
-                    }
-                }
-            }
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) X[i][nt] = join(cvt4(xacc[0][nt]), cvt4(xacc[1][nt]));
-
-            if (isV) {
-                // U' tiles are accumulator tiles as they stand: one contiguous 512 B store each
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt)
-                        st4(Ug + ((size_t)((2 * i + mi) * DT + cb / 16 + nt) * 64 + lane) * 4, cvt4(xacc[mi][nt]));
-            } else {
-                // -W as A-operand tiles: transpose the 32 x FW tile through a wave-private LDS tile
-                bf16 *Ws = WsAll + w * 32 * WP;
-#pragma unroll
-                for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) {
-                        bf16x4 v = cvt4(-xacc[mi][nt]);
-#pragma unroll
-                        for (int jj = 0; jj < 4; ++jj) Ws[(16 * mi + 4 * g + jj) * WP + 16 * nt + r16] = v[jj];
-                    }
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                // this wave's columns are features [cb, cb + FW); lane (r16, g) of k-step ks holds
-                // features 32 ks + 8 g .. + 7
-                const int ks = cb / 32, fo = cb % 32;
-                if (8 * g >= fo && 8 * g < fo + FW) {
+            for (int sl = 0; sl < SPW; ++sl) {
+                const int s = sl == 0 ? w : NS - 1 - w;          // slice: columns 16 s .. 16 s + 15 of X
+                const bool have = sl == 0 ? (w < NS) : true;
+                const int ib = s >> 1;                            // block that holds the slice's diagonal
+                if (have && ib >= j) {                            // otherwise X_j is zero on this slice
+                    f32x4 acc[2];
+                    // right-hand side E_j: the identity, non-zero only on the slice's own block
 #pragma unroll
                     for (int mi = 0; mi < 2; ++mi)
-                        st8(Wg + ((size_t)((2 * i + mi) * NKS + ks) * 64 + lane) * 8,
-                            ld8(&Ws[(16 * mi + r16) * WP + 8 * g - fo]));
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            acc[mi][e] = (ib == j && (s & 1) == mi && 4 * g + e == r16) ? 1.0f : 0.0f;
+                    // minus sum_{i > j} G_ij^T X_i  (G stored negated); X_i = 0 beyond the slice's block
+#pragma unroll
+                    for (int i = 0; i < NB; ++i) {
+                        if (i > j && i <= ib) {
+#pragma unroll
+                            for (int mi = 0; mi < 2; ++mi) {
+                                bf16x8 a = join(ld4(&Gb[(16 * mi + r16) * GP + 32 * i + 4 * g]),
+                                                ld4(&Gb[(16 * mi + r16) * GP + 32 * i + 16 + 4 * g]));
+                                acc[mi] = mfma16(a, X[sl][i], acc[mi]);
+                            }
+                        }
+                    }
+                    // X_j = T_jj^T R_j
+                    bf16x8 rb = join(cvt4(acc[0]), cvt4(acc[1]));
+                    f32x4 xacc[2];
+#pragma unroll
+                    for (int mi = 0; mi < 2; ++mi) {
+                        bf16x8 a = join(ld4(&Ts[(j * 32 + 16 * mi + r16) * TP + 4 * g]),
+                                        ld4(&Ts[(j * 32 + 16 * mi + r16) * TP + 16 + 4 * g]));
+                        f32x4 z = {0.f, 0.f, 0.f, 0.f};
+                        xacc[mi] = mfma16(a, rb, z);
+                    }
+                    X[sl][j] = join(cvt4(xacc[0]), cvt4(xacc[1]));
+                    // lane (r16, g) now holds T[16 s + r16][32 j + 4 g + e] (e < 4) and
+                    // T[16 s + r16][32 j + 16 + 4 g + e - 4] (e >= 4): the A-operand tile (s, j) as is.
+                    st8(Ttg + ((size_t)(s * NKT + j) * 64 + lane) * 8, X[sl][j]);
                 }
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             }
             __syncthreads();
         }
 
-        // ------------------------------------------------------------ P = Mbar (.) Q K^T, Q tiles
+        // ------------------------------------------------------------ P = Mbar (.) Q K^T
 #pragma unroll
         for (int q = 0; q < QV; ++q) {
             const int v = tid + NTHR * q;
             if ((q + 1) * NTHR <= C * D / 8 || v < C * D / 8) st8(&Qs[(v / VPR) * KP + (v % VPR) * 8], qreg[q]);
         }
         __syncthreads();
-        if (more) fetch_q(nxt);
+        fetch_q(nxt);
         for (int it = w; it < CT * NKT; it += kFlowWaves) {
             const int tt = it / NKT, kt = it % NKT;
             if (32 * kt >= R * (16 * tt + 16)) continue;       // wholly after the last visible token
             bf16x8 bq[NKS];
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) bq[ks] = ld8(&Qs[(16 * tt + r16) * KP + 32 * ks + 8 * g]);
-            if (kt == 0) {
-#pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) st8(Qtg + ((size_t)(tt * NKS + ks) * 64 + lane) * 8, bq[ks]);
-            }
             f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
@@ -431,9 +365,8 @@ bool mfma_instance_exists(int d, int n, int chunk)
 }
 
 template <int D, int N, int C>
-static hipError_t launch_flow_instance(const void *Q, const void *K, const void *V, const void *beta,
-                                       void *Wt, void *Ut, void *Kt, void *Pt, void *Qt, size_t nchunks,
-                                       hipStream_t stream)
+static hipError_t launch_flow_instance(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,
+                                       size_t nchunks, hipStream_t stream)
 {
     auto kern = flow_kernel<D, N, C>;
     constexpr size_t lds = FlowLds<D, N, C>::total;
@@ -442,27 +375,25 @@ static hipError_t launch_flow_instance(const void *Q, const void *K, const void 
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     // Persistent grid: as many workgroups as the chip holds at once (LDS decides how many per
-    // CU), each walking its share of the chunks.
+    // CU, at most two), each walking its share of the chunks.
     const size_t per_cu = kMaxLdsBytes / lds ? kMaxLdsBytes / lds : 1;
     const size_t resident = kNumCUs * (per_cu > 2 ? 2 : per_cu);
     const unsigned grid = (unsigned)(nchunks < resident ? nchunks : resident);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kFlowThreads), lds, stream, (const bf16 *)Q,
-                       (const bf16 *)K, (const bf16 *)V, (const bf16 *)beta, (bf16 *)Wt, (bf16 *)Ut,
-                       (bf16 *)Kt, (bf16 *)Pt, (bf16 *)Qt, (int)nchunks);
+                       (const bf16 *)K, (const bf16 *)beta, (bf16 *)Tt, (bf16 *)Pt, (int)nchunks);
     return hipGetLastError();
 }
 
-hipError_t launch_chunk_flow(const void *Q, const void *K, const void *V, const void *beta, void *Wt,
-                             void *Ut, void *Kt, void *Pt, void *Qt, int heads, int L, int d, int r,
-                             int chunk, hipStream_t stream)
+hipError_t launch_chunk_flow(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,
+                             int heads, int L, int d, int r, int chunk, hipStream_t stream)
 {
     const size_t nchunks = (size_t)heads * (L / chunk);
     if (nchunks == 0) return hipSuccess;
     if (nchunks > 0x7fffffffull) return hipErrorInvalidValue;
     const int n = chunk * r;
-#define X(DD, NN, CC)                                                                                 \
-    if (d == DD && n == NN && chunk == CC)                                                             \
-        return launch_flow_instance<DD, NN, CC>(Q, K, V, beta, Wt, Ut, Kt, Pt, Qt, nchunks, stream);
+#define X(DD, NN, CC)                                                                        \
+    if (d == DD && n == NN && chunk == CC)                                                    \
+        return launch_flow_instance<DD, NN, CC>(Q, K, beta, Tt, Pt, nchunks, stream);
     PF_FLOW_INSTANCES(X)
 #undef X
     return hipErrorInvalidValue;

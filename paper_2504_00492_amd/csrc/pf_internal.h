@@ -18,11 +18,10 @@ hipError_t launch_generic(const void *Q, const void *K, const void *V, const voi
 
 // ---- MFMA path (pf_flow.hip, pf_scan.hip); d = d_k = d_v, n = chunk * r
 bool mfma_instance_exists(int d, int n, int chunk);
-hipError_t launch_chunk_flow(const void *Q, const void *K, const void *V, const void *beta,
-                             void *Wt, void *Ut, void *Kt, void *Pt, void *Qt,
+hipError_t launch_chunk_flow(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,
                              int heads, int L, int d, int r, int chunk, hipStream_t stream);
-hipError_t launch_chunk_scan(const void *Wt, const void *Ut, const void *Kt, const void *Pt,
-                             const void *Qt, const float *S0, void *O, float *SL,
+hipError_t launch_chunk_scan(const void *Q, const void *K, const void *V, const void *beta,
+                             const void *Tt, const void *Pt, const float *S0, void *O, float *SL,
                              int heads, int L, int d, int r, int chunk, hipStream_t stream);
 
 }  // namespace pf

@@ -80,44 +80,49 @@ def test_empty_sequence_returns_initial_state(pf):
 # ------------------------------------------------------------------ chunk flow (Theorem 3.2) on its own
 @pytest.mark.parametrize("d,r,C", [(64, 1, 64), (128, 2, 64), (128, 4, 64), (128, 2, 128), (128, 1, 128), (64, 4, 64)])
 def test_chunk_flow_matches_theorem(pf, oracle, d, r, C):
-    """W, U', K, P and Q of every chunk (decoded from their tiled layouts) against the numpy
-    statement of Theorem 3.2; then the scan entry point on those arrays against the oracle."""
+    """T and P of every chunk (decoded from their tiled layouts) against the numpy statement of
+    Theorem 3.2: T is the inverse of the system matrix, T (beta K) = W and T (beta V) = -U; then the
+    scan entry point on those arrays against the oracle."""
     import torch
     from oracle import chunk_flow_ref as cf
-    from gpu_util import untile_rows8, untile_acc4
+    from gpu_util import untile_rows8
     w = synth.Workload("flow", "bf16", 1, 2, 2 * C, d, d, r, C, seed=21, reflect_frac=0.1)
     _say(f"[case] chunk flow d={d} r={r} C={C}")
     inp = synth.make_inputs(w)
     dev = to_device(w, inp)
     n, NC = C * r, w.L // C
     mk = lambda m: torch.full((1, 2, NC, m), float("nan"), dtype=torch.bfloat16, device="cuda:0")
-    Wt, Ut, Kt, Pt, Qt = mk(n * d), mk(n * d), mk(n * d), mk(C * n), mk(C * d)
-    st = pf.pf_delta_chunk_flow(dev["Q"], dev["K"], dev["V"], dev["beta"], Wt, Ut, Kt, Pt, Qt, 1, 2, w.L, d, d, r, C)
+    Tt, Pt = mk(n * n), mk(C * n)
+    st = pf.pf_delta_chunk_flow(dev["Q"], dev["K"], dev["beta"], Tt, Pt, 1, 2, w.L, d, d, r, C)
     assert st == pf.PF_OK
     O = torch.empty(1, 2, w.L, d, dtype=torch.bfloat16, device="cuda:0")
     SL = torch.empty(1, 2, d, d, dtype=torch.float32, device="cuda:0")
-    st = pf.pf_delta_chunk_scan(Wt, Ut, Kt, Pt, Qt, None, O, SL, 1, 2, w.L, d, d, r, C)
+    st = pf.pf_delta_chunk_scan(dev["Q"], dev["K"], dev["V"], dev["beta"], Tt, Pt, None, O, SL, 1, 2, w.L, d, d, r, C)
     assert st == pf.PF_OK
     torch.cuda.synchronize()
-    Wt, Ut, Kt, Pt, Qt = (t.float().cpu().numpy() for t in (Wt, Ut, Kt, Pt, Qt))
-    MT, NKT, DT, NKS, CT = n // 16, n // 32, d // 16, d // 32, C // 16
+    Tt, Pt = (t.float().cpu().numpy() for t in (Tt, Pt))
+    MT, NKT, CT = n // 16, n // 32, C // 16
+    rows = np.arange(n)
     for h in range(2):
         for c in range(NC):
             sl = slice(c * C, (c + 1) * C)
             A, At, Bm = cf.delta_drivers(inp["K"][h, sl], inp["V"][h, sl], inp["beta"][h, sl])
-            Wr, Ur = cf.chunk_flow(A, At, Bm)                     # paper's W and U (= -U')
+            Wr, Ur = cf.chunk_flow(A, At, Bm)                     # paper's W and U
+            Tr = cf.block_tri_inverse(cf.system_matrix(A, Bm), r)
             Kf = inp["K"][h, sl].reshape(n, d).astype(np.float64)
             mask = cf.inclusive_time_mask(C, r)
             Pr = mask * (inp["Q"][h, sl].astype(np.float64) @ Kf.T)
-            Wg = untile_rows8(Wt[0, h, c], MT, NKS)
-            Ug = untile_acc4(Ut[0, h, c], MT, DT)
-            Kg = untile_rows8(Kt[0, h, c], DT, NKT).T
-            Qg = untile_rows8(Qt[0, h, c], CT, NKS)
+            Tg = untile_rows8(Tt[0, h, c], MT, NKT, relabel=True)
             Pg = untile_rows8(Pt[0, h, c], CT, NKT, relabel=True)
-            assert rel_l2(Wg, -Wr) < 1e-2
-            assert rel_l2(Ug, -Ur) < 1e-2
-            assert np.array_equal(Kg, inp["K"][h, sl].reshape(n, d))
-            assert np.array_equal(Qg, inp["Q"][h, sl])
+            # T: tiles (mt, kt) with 2 kt <= mt are written, the rest untouched (NaN) and zero in T
+            tile_written = (2 * (rows[None, :] // 32) <= rows[:, None] // 16)
+            assert np.array_equal(~np.isnan(Tg), tile_written)
+            assert np.all(Tr[~tile_written] == 0)
+            Tz = np.where(tile_written, Tg, 0.0)
+            assert rel_l2(Tz, Tr) < 1e-2
+            assert np.all(Tz[np.triu_indices(n, 1)] == 0)         # exactly lower triangular
+            assert rel_l2(Tz @ A.reshape(n, d), Wr) < 1e-2        # W of Theorem 3.2
+            assert rel_l2(Tz @ At.reshape(n, d), Ur) < 1e-2       # U of Theorem 3.2
             # P: written tiles carry zeros behind the mask; tiles wholly behind it stay untouched (NaN)
             written = ~np.isnan(Pg)
             assert np.all(written[mask == 1])
