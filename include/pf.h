@@ -64,10 +64,18 @@ const char *pf_status_str(pf_status s);
  *   1  generic path: one workgroup per (b, h), fp32 vector arithmetic, chunk state in LDS;
  *      any d_k, d_v, r, chunk whose per-chunk working set fits 160 KiB of LDS; both dtypes;
  *      L need not be a multiple of chunk (the tail is a shorter last chunk)
- *   2  MFMA path (PF_BF16 only): d_k = d_v in {64, 128}, n = chunk * r in {64, 128, 256},
- *      chunk in {64, 128}, L a multiple of chunk
+ *   2  MFMA path (PF_BF16 only): d_k = d_v in {64, 128}, L a multiple of chunk, and a flow
+ *      block (see pf_delta_fwd_block) with block * r in {64, 128, 256}, block in {64, 128}
  */
 int pf_delta_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt);
+
+/* Tokens per flow block the MFMA path uses for these dimensions: chunk itself when chunk * r
+ * virtual tokens fit a kernel instance (at most 256), else chunk / 2^j for the smallest j that
+ * does.  The flow over a chunk is the composition of the flows over consecutive pieces of it
+ * (Section 3.1), so O and S_L are the same function of the inputs either way; only the
+ * blocking of the arithmetic, hence its rounding, differs.  0 when pf_delta_fwd_supported(...)
+ * is not 2.  Host only. */
+int pf_delta_fwd_block(int d_k, int d_v, int r, int chunk, pf_dtype dt);
 
 /* Bytes of device scratch pf_delta_fwd needs for these dimensions (0 for the generic path and
  * for unsupported dimensions).  Host only. */
@@ -103,7 +111,8 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
 
 /*
  * Step 2 of Section 3 on its own ("parallel compute": the flow of every chunk, no dependence
- * between chunks), MFMA path only (pf_delta_fwd_supported(...) == 2).  With n = chunk * r,
+ * between chunks), MFMA path only and only for chunk == pf_delta_fwd_block(...) (else
+ * PF_ERR_UNSUPPORTED).  With n = chunk * r,
  * d = d_k = d_v and NC = L / chunk, for every (b, h, c):
  *
  *   Cmat = Id + M (.) diag(beta) K K^T,  M[(t,i),(s,j)] = 1 iff s < t     (Theorem 3.2 in delta

@@ -13,7 +13,7 @@ _LIB_PATH = os.path.join(_HERE, "libpf.so")
 PF_OK, PF_ERR_NULL, PF_ERR_SHAPE, PF_ERR_UNSUPPORTED, PF_ERR_ALIGN, PF_ERR_WORKSPACE, PF_ERR_LAUNCH = range(7)
 PF_F32, PF_BF16 = 0, 1
 
-EXPORTS = ["pf_version", "pf_status_str", "pf_delta_fwd_supported", "pf_delta_fwd_workspace_bytes",
+EXPORTS = ["pf_version", "pf_status_str", "pf_delta_fwd_supported", "pf_delta_fwd_block", "pf_delta_fwd_workspace_bytes",
            "pf_delta_fwd", "pf_delta_chunk_flow", "pf_delta_chunk_scan"]
 
 
@@ -35,6 +35,8 @@ def _load() -> ctypes.CDLL:
     lib.pf_status_str.argtypes = [i]
     lib.pf_delta_fwd_supported.restype = i
     lib.pf_delta_fwd_supported.argtypes = [i, i, i, i, i]
+    lib.pf_delta_fwd_block.restype = i
+    lib.pf_delta_fwd_block.argtypes = [i, i, i, i, i]
     lib.pf_delta_fwd_workspace_bytes.restype = sz
     lib.pf_delta_fwd_workspace_bytes.argtypes = [i] * 8
     lib.pf_delta_fwd.restype = i
@@ -77,6 +79,10 @@ def pf_status_str(status: int) -> str:
 
 def pf_delta_fwd_supported(d_k, d_v, r, chunk, dt) -> int:
     return int(_lib.pf_delta_fwd_supported(d_k, d_v, r, chunk, dt))
+
+
+def pf_delta_fwd_block(d_k, d_v, r, chunk, dt) -> int:
+    return int(_lib.pf_delta_fwd_block(d_k, d_v, r, chunk, dt))
 
 
 def pf_delta_fwd_workspace_bytes(B, H, L, d_k, d_v, r, chunk, dt) -> int:

@@ -27,13 +27,24 @@ WorkspacePlan plan_workspace(int heads, int L, int d, int r, int chunk)
     return p;
 }
 
+// Tokens per flow block on the MFMA path: the requested chunk, halved until chunk * r virtual
+// tokens fit a kernel instance (the flow over a chunk is the composition of the flows over
+// its halves, Section 3.1).  0 when no instance serves these dimensions.
+int mfma_block(int d_k, int d_v, int r, int chunk, pf_dtype dt)
+{
+    if (dt != PF_BF16 || d_k != d_v) return 0;
+    for (int c = chunk; c >= 16; c /= 2) {
+        if ((long long)c * r <= 4096 && pf::mfma_instance_exists(d_k, c * r, c)) return c;
+        if (c % 2 != 0) break;
+    }
+    return 0;
+}
+
 int family(int d_k, int d_v, int r, int chunk, pf_dtype dt)
 {
     if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return 0;
     if (dt != PF_F32 && dt != PF_BF16) return 0;
-    if (dt == PF_BF16 && d_k == d_v && (long long)chunk * r <= 4096 &&
-        pf::mfma_instance_exists(d_k, chunk * r, chunk))
-        return 2;
+    if (mfma_block(d_k, d_v, r, chunk, dt) > 0) return 2;
     if ((long long)chunk * r > 65536 || d_k > 65536 || d_v > 65536) return 0;
     if (pf::generic_lds_bytes(d_k, d_v, r, chunk) <= pf::kMaxLdsBytes) return 1;
     return 0;
@@ -71,11 +82,17 @@ int pf_delta_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt)
     return family(d_k, d_v, r, chunk, dt);
 }
 
+int pf_delta_fwd_block(int d_k, int d_v, int r, int chunk, pf_dtype dt)
+{
+    if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return 0;
+    return mfma_block(d_k, d_v, r, chunk, dt);
+}
+
 size_t pf_delta_fwd_workspace_bytes(int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt)
 {
     if (check_dims(B, H, L, d_k, d_v, r, chunk) != PF_OK) return 0;
     if (family(d_k, d_v, r, chunk, dt) != 2 || L % chunk != 0) return 0;
-    return plan_workspace(B * H, L, d_k, r, chunk).total;
+    return plan_workspace(B * H, L, d_k, r, mfma_block(d_k, d_v, r, chunk, dt)).total;
 }
 
 pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
@@ -101,13 +118,14 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
                                           dt == PF_BF16, s);
         return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
     }
-    const WorkspacePlan wp = plan_workspace(heads, L, d_k, r, chunk);
+    const int block = mfma_block(d_k, d_v, r, chunk, dt);
+    const WorkspacePlan wp = plan_workspace(heads, L, d_k, r, block);
     if (!workspace || workspace_bytes < wp.total) return PF_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PF_ERR_ALIGN;
     char *ws = static_cast<char *>(workspace);
-    hipError_t e = pf::launch_chunk_flow(Q, K, beta, ws + wp.oT, ws + wp.oP, heads, L, d_k, r, chunk, s);
+    hipError_t e = pf::launch_chunk_flow(Q, K, beta, ws + wp.oT, ws + wp.oP, heads, L, d_k, r, block, s);
     if (e != hipSuccess) return PF_ERR_LAUNCH;
-    e = pf::launch_chunk_scan(Q, K, V, beta, ws + wp.oT, ws + wp.oP, S0, O, S_L, heads, L, d_k, r, chunk, s);
+    e = pf::launch_chunk_scan(Q, K, V, beta, ws + wp.oT, ws + wp.oP, S0, O, S_L, heads, L, d_k, r, block, s);
     return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
 }
 
@@ -117,7 +135,7 @@ pf_status pf_delta_chunk_flow(const void *Q, const void *K, const void *beta, vo
     if (!Q || !K || !beta || !Tt || !Pt) return PF_ERR_NULL;
     pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
     if (st != PF_OK) return st;
-    if (family(d_k, d_v, r, chunk, PF_BF16) != 2) return PF_ERR_UNSUPPORTED;
+    if (mfma_block(d_k, d_v, r, chunk, PF_BF16) != chunk) return PF_ERR_UNSUPPORTED;
     if (L % chunk != 0) return PF_ERR_SHAPE;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(beta) || !aligned16(Tt) || !aligned16(Pt))
         return PF_ERR_ALIGN;
@@ -134,7 +152,7 @@ pf_status pf_delta_chunk_scan(const void *Q, const void *K, const void *V, const
     if (!Q || !K || !V || !beta || !Tt || !Pt || !O) return PF_ERR_NULL;
     pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
     if (st != PF_OK) return st;
-    if (family(d_k, d_v, r, chunk, PF_BF16) != 2) return PF_ERR_UNSUPPORTED;
+    if (mfma_block(d_k, d_v, r, chunk, PF_BF16) != chunk) return PF_ERR_UNSUPPORTED;
     if (L % chunk != 0) return PF_ERR_SHAPE;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(beta) || !aligned16(Tt) ||
         !aligned16(Pt) || !aligned16(S0) || !aligned16(O) || !aligned16(S_L))

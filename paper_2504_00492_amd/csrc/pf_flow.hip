@@ -371,9 +371,17 @@ static hipError_t launch_flow_instance(const void *Q, const void *K, const void 
     auto kern = flow_kernel<D, N, C>;
     constexpr size_t lds = FlowLds<D, N, C>::total;
     static_assert(lds <= kMaxLdsBytes, "flow kernel LDS plan exceeds the CU");
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    // the LDS opt-in is per device and sticks: ask once per device, not once per launch
+    static int armed_device = -1;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
+    if (armed_device != dev) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        armed_device = dev;
+    }
     // Persistent grid: as many workgroups as the chip holds at once (LDS decides how many per
     // CU, at most two), each walking its share of the chunks.
     const size_t per_cu = kMaxLdsBytes / lds ? kMaxLdsBytes / lds : 1;

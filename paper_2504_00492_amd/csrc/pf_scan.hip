@@ -9,35 +9,47 @@
 //     O_c   = Q S_c^T + P U_eff           chunk x TV   (discrete flow of Section 3.1 cut at each token)
 //     S_c+1 = S_c + U_eff^T K             TV x d       (S_1 of Theorem 3.2)
 //
-// Data movement.  S^T lives in fp32 accumulators (wave w owns d_k rows [w d/4, (w+1) d/4)); a
-// bf16 copy in LDS ([d_v][d_k], double buffered) feeds the MFMA operands of the next chunk.
-// K, the V tile, Q and beta of a chunk are fetched one chunk ahead into registers with
-// coalesced 16-byte loads and staged in LDS at the top of the step; K is read from there both
-// row-wise (K S^T) and, through the LDS transposing read, column-wise (K^T U_eff); the V tile is
-// read transposed into accumulator layout.  R and U_eff go through LDS once each ([d_v][n]:
-// accumulator tiles are 4 consecutive tokens of one feature, i.e. 8-byte writes).  T and P
-// tiles are used by exactly one wave each and are loaded straight from global memory into MFMA
-// operand registers, one contiguous tile per load, one chunk ahead.  O is computed transposed
-// (rows = d_v) so that a lane ends up with 4 consecutive features of one token.
+// Only R -> U_eff -> S_c+1 is a chain from one chunk to the next; the readout O_c hangs off it.
+// The workgroup therefore has two kinds of wavefronts, one of each per SIMD:
 //
-// Every fetch is unconditional and branch-free (tiles that are not needed re-read a tile that
-// is), because a branch around a load makes every later wait assume the shorter queue.  Where
-// the register budget allows a fifth wave (n <= 128), the four compute waves issue no global
-// stores inside the chunk loop: O tiles go to LDS and the fifth wave copies them out one step
-// later.  With only loads in flight, a wave's memory counter retires in order, so waiting for
-// one operand set does not also wait for the sets requested after it.  For n = 256 the operand
-// sets need more than 256 registers per lane, which only four waves per workgroup leave room
-// for; there the compute waves store O themselves.
+//   state waves (0..3)  run the chain and nothing else: R (interval 0), U_eff (interval 1),
+//                       S update (interval 2).  Their only global loads are their own T tiles,
+//                       straight into MFMA operand registers, one chunk ahead.
+//   io waves (4..7)     do everything that can be late or early: Q S^T (interval 0), staging of
+//                       the next chunk's K, V tile, Q, beta from registers into LDS and the
+//                       loads of the chunk after it (interval 1), U_eff^T P^T and the O tile
+//                       (interval 2), and the coalesced copy of the previous O tile to global
+//                       memory.  Their load-issue stalls and LDS stores overlap the chain.
+//
+// S^T lives in fp32 accumulators of the state waves (wave w owns d_k rows [w d/4, (w+1) d/4)); a
+// bf16 copy in LDS ([d_v][d_k]) feeds the MFMA operands of the next chunk.  K is read from LDS
+// both row-wise (K S^T) and, through the LDS transposing read, column-wise (K^T U_eff); the V
+// tile is read transposed into accumulator layout.  R and U_eff go through LDS once each
+// ([d_v][n]: accumulator tiles are 4 consecutive tokens of one feature, i.e. 8-byte writes).  O
+// is computed transposed (rows = d_v) so that a lane ends up with 4 consecutive features of one
+// token.  K is needed in intervals 0 and 2, so the next chunk's K can only be staged during
+// interval 1 into a second buffer; where two K buffers do not fit LDS (n = 256 with d = 128) a
+// fourth interval is opened at the end of the step in which the io waves overwrite K in place.
+// V, Q, beta, the state copy and the O tile are each written in one interval and read in another
+// and need one buffer.
+//
+// The wave id is a compile-time constant of each wave's code (the kernel branches once on it):
+// the triangular bounds of T R and of the causal readout then prune whole MFMAs and loads at
+// compile time, leaving straight-line code in which LDS reads can be scheduled ahead of the
+// MFMAs that use them.  Every fetch is unconditional, the last step re-fetches its own chunk.
 #include "pf_internal.h"
 #include "pf_common.cuh"
 #include "pf_layout.h"
 
+#include <type_traits>
+
 namespace pf {
 
-constexpr int kScanComputeWaves = 4;
-constexpr int kScanComputeThreads = 64 * kScanComputeWaves;
-template <int N> constexpr bool scan_has_writer() { return N <= 128; }
-template <int N> constexpr int scan_threads() { return kScanComputeThreads + (scan_has_writer<N>() ? 64 : 0); }
+#define LDS_FENCE() asm volatile("" ::: "memory")
+
+constexpr int kScanRoleWaves = 4;                       // waves per role
+constexpr int kScanRoleThreads = 64 * kScanRoleWaves;
+constexpr int kScanThreads = 2 * kScanRoleThreads;
 
 template <int D, int N, int C, int TV>
 struct ScanLds {
@@ -46,19 +58,23 @@ struct ScanLds {
     static constexpr int SP = D + 8;   // pitch of a row of the bf16 state copy
     static constexpr int UP = N + 8;   // pitch of a row of R^T / U_eff^T
     static constexpr int OP = TV + 8;  // pitch of a row (one token) of the staged O tile
+    static constexpr size_t szK = (size_t)N * KP * 2;
+    static constexpr size_t rest = (size_t)N * VP * 2 + (size_t)C * KP * 2 + (size_t)N * 4 +
+                                   (size_t)TV * SP * 2 + (size_t)2 * TV * UP * 2 + (size_t)C * OP * 2;
+    static constexpr bool kDoubleK = 2 * szK + rest <= (size_t)kMaxLdsBytes;
     static constexpr size_t oKs = 0;
-    static constexpr size_t oVs = oKs + (size_t)N * KP * 2;
+    static constexpr size_t oVs = oKs + (kDoubleK ? 2 : 1) * szK;
     static constexpr size_t oQs = oVs + (size_t)N * VP * 2;
     static constexpr size_t oBs = oQs + (size_t)C * KP * 2;
     static constexpr size_t oSb = oBs + (size_t)N * 4;
-    static constexpr size_t oRs = oSb + (size_t)2 * TV * SP * 2;
+    static constexpr size_t oRs = oSb + (size_t)TV * SP * 2;
     static constexpr size_t oUe = oRs + (size_t)TV * UP * 2;
     static constexpr size_t oOb = oUe + (size_t)TV * UP * 2;
-    static constexpr size_t total = oOb + (scan_has_writer<N>() ? (size_t)2 * C * OP * 2 : 0);
+    static constexpr size_t total = oOb + (size_t)C * OP * 2;
 };
 
 template <int D, int N, int C, int TV>
-__global__ __launch_bounds__(scan_threads<N>()) void scan_kernel(
+__global__ __launch_bounds__(kScanThreads) void scan_kernel(
     const bf16 *__restrict__ Q, const bf16 *__restrict__ K, const bf16 *__restrict__ V,
     const bf16 *__restrict__ beta, const bf16 *__restrict__ Tt, const bf16 *__restrict__ Pt,
     const float *S0, bf16 *__restrict__ O, float *SL, int nchains, int NC)
@@ -70,14 +86,15 @@ __global__ __launch_bounds__(scan_threads<N>()) void scan_kernel(
     constexpr int NNT = TV / 16;       // 16-wide tiles over this workgroup's d_v rows
     constexpr int MT = N / 16;         // 16-row tiles of virtual tokens
     constexpr int CT = C / 16;         // 16-row tiles of tokens
-    constexpr int MPW = D / 64;        // d_k tiles (16 rows of S^T) owned by one wave
-    constexpr int M1 = MT / 4;         // 16-row tiles of R / U_eff per wave
-    constexpr int T2 = CT / 4;         // 16-token tiles of O per wave
+    constexpr int MPW = D / 64;        // d_k tiles (16 rows of S^T) owned by one state wave
+    constexpr int M1 = MT / 4;         // 16-row tiles of R / U_eff per state wave
+    constexpr int T2 = CT / 4;         // 16-token tiles of O per io wave
     constexpr int KP = Ld::KP, VP = Ld::VP, SP = Ld::SP, UP = Ld::UP, OP = Ld::OP;
-    constexpr int NTHR = kScanComputeThreads;
-    constexpr bool kWriter = scan_has_writer<N>();
+    constexpr int NTHR = kScanRoleThreads;
+    constexpr bool kDoubleK = Ld::kDoubleK;
     static_assert(D % 64 == 0 && TV % 16 == 0 && N % 32 == 0, "tile shapes");
-    static_assert(MT % 4 == 0 && CT % 4 == 0, "every compute wave owns the same number of tiles");
+    static_assert(MT % 4 == 0 && CT % 4 == 0, "every wave of a role owns the same number of tiles");
+    static_assert(N <= NTHR, "beta of a chunk is fetched by one pass");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16 *Ks = reinterpret_cast<bf16 *>(smem + Ld::oKs);
@@ -89,280 +106,388 @@ __global__ __launch_bounds__(scan_threads<N>()) void scan_kernel(
     bf16 *Ue = reinterpret_cast<bf16 *>(smem + Ld::oUe);
     bf16 *Ob = reinterpret_cast<bf16 *>(smem + Ld::oOb);
 
-    const int tid0 = threadIdx.x;
-    int tid = tid0;
-    int w = tid >> 6, lane = tid & 63;
-    int r16 = lane & 15, g = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane0 = threadIdx.x & 63;
 
     // Workgroups of one (b, h) are nchains apart in blockIdx, hence on the same XCD (block ids
     // go round-robin over the 8 XCDs) and share that XCD's L2 for K, Q, T and P, which they all read.
     const int tile = blockIdx.x / nchains;
     const size_t chain = blockIdx.x % nchains;
     const int dv0 = tile * TV;
+    const size_t c0 = chain * (size_t)NC;
 
-    if (kWriter && w == kScanComputeWaves) {
-        // ---- writer wave: after each step's closing barrier, copy that step's O tile
-        // (chunk tokens x TV features) from LDS to its rows of O.  It takes part in every
-        // barrier of the compute waves and touches nothing else.
-        constexpr int PPT = TV / 8;              // 16-byte pieces per token
-        constexpr int TPI = 64 / PPT;            // tokens per pass of the wave
-        __syncthreads();                         // pairs with the barrier after the initial state
-        for (int ch = 0; ch < NC; ++ch) {
-            __syncthreads();
-            __syncthreads();
-            __syncthreads();
-            __syncthreads();
-            const bf16 *src = Ob + (ch & 1) * C * OP;
-            bf16 *Oc = O + (chain * (size_t)NC + ch) * (size_t)C * D;
+    // ------------------------------------------------------------------ state waves
+    auto state_wave = [&](auto Wc) {
+        constexpr int W = decltype(Wc)::value;
+        int lane = lane0, r16 = lane & 15, g = lane >> 4;
+
+        // rows of U_eff owned by this wave: tiles W and 7 - W of every group of 8 (evens out
+        // the triangular amount of work of T R); one tile per wave when there are only 4
+        constexpr auto row_tile = [](int i) constexpr { return MT >= 8 ? ((i & 1) ? 8 * (i >> 1) + 7 - W : 8 * (i >> 1) + W) : W + 4 * i; };
+
+        f32x4 sacc[MPW][NNT];
 #pragma unroll
-            for (int t0 = 0; t0 < C; t0 += TPI) {
-                const int t = t0 + lane / PPT, pc = lane % PPT;
-                st8(Oc + (size_t)t * D + dv0 + 8 * pc, ld8(&src[t * OP + 8 * pc]));
+        for (int a = 0; a < MPW; ++a)
+#pragma unroll
+            for (int nt = 0; nt < NNT; ++nt) {
+                const int mt = W * MPW + a;
+                f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                if (S0) v = *reinterpret_cast<const f32x4 *>(S0 + chain * (size_t)D * D +
+                                                             (size_t)(dv0 + 16 * nt + r16) * D + 16 * mt + 4 * g);
+                sacc[a][nt] = v;
+                st4(&Sb[(16 * nt + r16) * SP + 16 * mt + 4 * g], cvt4(v));
             }
-        }
-        return;
-    }
 
-    // ---- initial state: fp32 accumulators + bf16 copy
-    f32x4 sacc[MPW][NNT];
-#pragma unroll
-    for (int a = 0; a < MPW; ++a)
-#pragma unroll
-        for (int nt = 0; nt < NNT; ++nt) {
-            const int mt = w * MPW + a;
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (S0) v = *reinterpret_cast<const f32x4 *>(S0 + chain * (size_t)D * D +
-                                                         (size_t)(dv0 + 16 * nt + r16) * D + 16 * mt + 4 * g);
-            sacc[a][nt] = v;
-            st4(&Sb[(16 * nt + r16) * SP + 16 * mt + 4 * g], cvt4(v));
-        }
-    __syncthreads();
-
-    // ---- register sets that carry the next chunk's operands
-    constexpr int VPR = D / 8;                                 // 16-byte vectors per row of K / Q
-    constexpr int KV = (N * D / 8 + NTHR - 1) / NTHR;          // vectors of K per thread
-    constexpr int QV = (C * D / 8 + NTHR - 1) / NTHR;          // vectors of Q per thread
-    constexpr int PPR = TV / 8;                                // 16-byte pieces per row of the V tile
-    constexpr int VV = (N * PPR + NTHR - 1) / NTHR;            // vectors of the V tile per thread
-    bf16x8 kreg[KV], qreg[QV], vreg[VV];
-    bf16 breg = (bf16)0.0f;
-    bf16x8 t1[M1][NKT];        // T tiles of this wave's rows of U_eff
-    bf16x8 p2[T2][NKT];        // P tiles of this wave's token tiles
-    static_assert(N <= NTHR, "beta of a chunk is fetched by one pass");
-
-    // rows of U_eff owned by this wave: tiles w and 7 - w of every group of 8 (evens out the
-    // triangular amount of work of T R); one tile per wave when there are only 4
-    auto row_tile = [&](int i) { return MT >= 8 ? ((i & 1) ? 8 * (i >> 1) + 7 - w : 8 * (i >> 1) + w) : w + 4 * i; };
-    // token tiles of O owned by this wave: w and (with 8 tiles) 7 - w
-    auto tok_tile = [&](int i) { return CT >= 8 ? ((i & 1) ? 8 * (i >> 1) + 7 - w : 8 * (i >> 1) + w) : w + 4 * i; };
-
-    auto fetch_in = [&](size_t cid) {
-        const bf16 *Kg = K + cid * (size_t)N * D;
-        const bf16 *Vg = V + cid * (size_t)N * D + dv0;
-        const bf16 *Qg = Q + cid * (size_t)C * D;
-#pragma unroll
-        for (int q = 0; q < KV; ++q) {
-            const int v = tid + NTHR * q;
-            if ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8) kreg[q] = ld8(Kg + (size_t)v * 8);
-        }
-#pragma unroll
-        for (int q = 0; q < VV; ++q) {
-            int v = tid + NTHR * q;
-            v = v < N * PPR ? v : N * PPR - 1;                 // clamp instead of branching
-            vreg[q] = ld8(Vg + (size_t)(v / PPR) * D + (v % PPR) * 8);
-        }
-#pragma unroll
-        for (int q = 0; q < QV; ++q) {
-            const int v = tid + NTHR * q;
-            if ((q + 1) * NTHR <= C * D / 8 || v < C * D / 8) qreg[q] = ld8(Qg + (size_t)v * 8);
-        }
-        breg = beta[cid * (size_t)N + (tid % N)];
-    };
-    auto fetch_t = [&](size_t cid) {
-        const bf16 *Tc = Tt + cid * (size_t)N * N;
-#pragma unroll
-        for (int i = 0; i < M1; ++i) {
-            const int mt = row_tile(i);
-#pragma unroll
-            for (int kt = 0; kt < NKT; ++kt) {
-                const int kk = 2 * kt <= mt ? kt : 0;          // tiles above the diagonal do not exist
-                t1[i][kt] = ld8(Tc + ((size_t)(mt * NKT + kk) * 64 + lane) * 8);
-            }
-        }
-    };
-    auto fetch_p = [&](size_t cid) {
-        const bf16 *Pc = Pt + cid * (size_t)C * N;
-#pragma unroll
-        for (int i = 0; i < T2; ++i) {
-            const int tt = tok_tile(i);
-            const int ksteps = (R * (16 * tt + 16) + 31) / 32;  // causal: virtual tokens < R (16 tt + 16)
-#pragma unroll
-            for (int kt = 0; kt < NKT; ++kt) {
-                const int kk = kt < ksteps ? kt : 0;
-                p2[i][kt] = ld8(Pc + ((size_t)(tt * NKT + kk) * 64 + lane) * 8);
-            }
-        }
-    };
-
-    if (NC > 0) {
-        fetch_in(chain * (size_t)NC);
-        fetch_t(chain * (size_t)NC);
-        fetch_p(chain * (size_t)NC);
-    }
-
-    for (int ch = 0; ch < NC; ++ch) {
-        // The thread id is laundered once per step so that the per-lane LDS and tile offsets of
-        // the unrolled code below are recomputed where they are used instead of being hoisted
-        // out of this loop and held in registers for the whole kernel.
-        tid = tid0;
-        asm volatile("" : "+v"(tid));
-        w = tid >> 6; lane = tid & 63; r16 = lane & 15; g = lane >> 4;
-        const int cur = ch & 1;
-        const size_t cid = chain * (size_t)NC + ch;
-        const size_t nx = ch + 1 < NC ? cid + 1 : cid;   // last step re-fetches its own chunk
-        bf16 *Ocur = Ob + cur * C * OP;
-        bf16 *Oc = O + cid * (size_t)C * D;
-        const bf16 *Scur = Sb + cur * TV * SP;
-
-        // ---- (0) this chunk's K, V tile, Q, beta: registers -> LDS; next chunk's on their way
-#pragma unroll
-        for (int q = 0; q < KV; ++q) {
-            const int v = tid + NTHR * q;
-            if ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8) st8(&Ks[(v / VPR) * KP + (v % VPR) * 8], kreg[q]);
-        }
-#pragma unroll
-        for (int q = 0; q < VV; ++q) {
-            const int v = tid + NTHR * q;
-            if (v < N * PPR) st8(&Vs[(v / PPR) * VP + (v % PPR) * 8], vreg[q]);
-        }
-#pragma unroll
-        for (int q = 0; q < QV; ++q) {
-            const int v = tid + NTHR * q;
-            if ((q + 1) * NTHR <= C * D / 8 || v < C * D / 8) st8(&Qs[(v / VPR) * KP + (v % VPR) * 8], qreg[q]);
-        }
-        if (tid < N) bs[tid] = (float)breg;
-        fetch_in(nx);
-        __syncthreads();
-
-        // ---- (1a) R = beta (.) (V - K S^T): rows (virtual tokens) dealt to the waves
-        {
-            bf16x8 bS[NNT][NKS];
-#pragma unroll
-            for (int nt = 0; nt < NNT; ++nt)
-#pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) bS[nt][ks] = ld8(&Scur[(16 * nt + r16) * SP + 32 * ks + 8 * g]);
+        bf16x8 t1[M1][NKT];        // T tiles of this wave's rows of U_eff (those below the diagonal)
+        auto fetch_t = [&](size_t cid) {
+            const bf16 *Tc = Tt + cid * (size_t)N * N;
 #pragma unroll
             for (int i = 0; i < M1; ++i) {
-                const int mt = w + 4 * i;
-                f32x4 acc[NNT];
+                const int mt = row_tile(i);
 #pragma unroll
-                for (int nt = 0; nt < NNT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < NKS; ++ks) {
-                    bf16x8 a = ld8(&Ks[(16 * mt + r16) * KP + 32 * ks + 8 * g]);
-#pragma unroll
-                    for (int nt = 0; nt < NNT; ++nt) acc[nt] = mfma16(a, bS[nt][ks], acc[nt]);
-                }
-                f32x4 bt;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) bt[e] = bs[16 * mt + 4 * g + e];
-#pragma unroll
-                for (int nt = 0; nt < NNT; ++nt) {
-                    // V tile read transposed: 4 consecutive tokens of feature 16 nt + r16
-                    bf16x4 v = lds_read_tr4(&Vs[(16 * mt + 4 * g + (r16 >> 2)) * VP + 16 * nt + 4 * (r16 & 3)]);
-                    f32x4 rr = (__builtin_convertvector(v, f32x4) - acc[nt]) * bt;
-                    st4(&Rs[(16 * nt + r16) * UP + 16 * mt + 4 * g], cvt4(rr));
-                }
+                for (int kt = 0; kt < NKT; ++kt)
+                    if (2 * kt <= mt) t1[i][kt] = ld8(Tc + ((size_t)(mt * NKT + kt) * 64 + lane) * 8);
             }
-        }
+        };
+        if (NC > 0) fetch_t(c0);
         __syncthreads();
 
-        // ---- (1b) U_eff = T R: lower block-triangular, rows dealt so that the waves do equal work
+        for (int ch = 0; ch < NC; ++ch) {
+            // The lane id is laundered once per step so that the per-lane LDS offsets of the
+            // unrolled code below are recomputed where they are used instead of being hoisted
+            // out of this loop and held in registers for the whole kernel.
+            lane = lane0;
+            asm volatile("" : "+v"(lane));
+            r16 = lane & 15; g = lane >> 4;
+            const size_t cid = c0 + ch;
+            const size_t nx = ch + 1 < NC ? cid + 1 : cid;   // last step re-fetches its own chunk
+            const bf16 *Kc = Ks + (kDoubleK ? (ch & 1) * N * KP : 0);
+
+            // Each interval first issues every LDS read it needs and only then starts its MFMAs
+            // (LDS_FENCE keeps the reads from sinking down to their first use), so that the
+            // read latency is paid once per interval instead of once per MFMA.
+
+            // ---- interval 0: R = beta (.) (V - K S^T), rows (virtual tokens) dealt to the waves
+            {
+                bf16x8 bS[NNT][NKS], aK[M1][NKS];
+                bf16x4 vt[M1][NNT];
+                f32x4 bt[M1];
 #pragma unroll
-        for (int i = 0; i < M1; ++i) {
-            const int mt = row_tile(i);
-            f32x4 acc[NNT];
+                for (int nt = 0; nt < NNT; ++nt)
 #pragma unroll
-            for (int nt = 0; nt < NNT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    for (int ks = 0; ks < NKS; ++ks) bS[nt][ks] = ld8(&Sb[(16 * nt + r16) * SP + 32 * ks + 8 * g]);
 #pragma unroll
-            for (int kt = 0; kt < NKT; ++kt) {
-                if (2 * kt <= mt) {
+                for (int i = 0; i < M1; ++i)
+#pragma unroll
+                    for (int ks = 0; ks < NKS; ++ks) aK[i][ks] = ld8(&Kc[(16 * (W + 4 * i) + r16) * KP + 32 * ks + 8 * g]);
+#pragma unroll
+                for (int i = 0; i < M1; ++i) {
+                    const int mt = W + 4 * i;
+                    bt[i] = *reinterpret_cast<const f32x4 *>(&bs[16 * mt + 4 * g]);
+                    // V tile read transposed: 4 consecutive tokens of feature 16 nt + r16
 #pragma unroll
                     for (int nt = 0; nt < NNT; ++nt)
-                        acc[nt] = mfma16(t1[i][kt],
-                                         join(ld4(&Rs[(16 * nt + r16) * UP + 32 * kt + 4 * g]),
-                                              ld4(&Rs[(16 * nt + r16) * UP + 32 * kt + 16 + 4 * g])),
-                                         acc[nt]);
+                        vt[i][nt] = lds_read_tr4(&Vs[(16 * mt + 4 * g + (r16 >> 2)) * VP + 16 * nt + 4 * (r16 & 3)]);
+                }
+                LDS_FENCE();
+#pragma unroll
+                for (int i = 0; i < M1; ++i) {
+                    const int mt = W + 4 * i;
+                    f32x4 acc[NNT];
+#pragma unroll
+                    for (int nt = 0; nt < NNT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+                        for (int nt = 0; nt < NNT; ++nt) acc[nt] = mfma16(aK[i][ks], bS[nt][ks], acc[nt]);
+#pragma unroll
+                    for (int nt = 0; nt < NNT; ++nt) {
+                        f32x4 rr = (__builtin_convertvector(vt[i][nt], f32x4) - acc[nt]) * bt[i];
+                        st4(&Rs[(16 * nt + r16) * UP + 16 * mt + 4 * g], cvt4(rr));
+                    }
+                }
+            }
+            __syncthreads();
+
+            // ---- interval 1: U_eff = T R, lower block-triangular, rows dealt so that the waves
+            // do equal work.  The R tiles (B operands) are shared by this wave's row tiles.
+            {
+                constexpr int KMAX = row_tile(M1 - 1) / 2 + 1 > row_tile(0) / 2 + 1 ? row_tile(M1 - 1) / 2 + 1
+                                                                                      : row_tile(0) / 2 + 1;
+                static_assert(KMAX <= NKT, "k-steps of T R");
+                bf16x8 bR[KMAX][NNT];
+#pragma unroll
+                for (int kt = 0; kt < KMAX; ++kt)
+#pragma unroll
+                    for (int nt = 0; nt < NNT; ++nt)
+                        bR[kt][nt] = join(ld4(&Rs[(16 * nt + r16) * UP + 32 * kt + 4 * g]),
+                                          ld4(&Rs[(16 * nt + r16) * UP + 32 * kt + 16 + 4 * g]));
+                LDS_FENCE();
+#pragma unroll
+                for (int i = 0; i < M1; ++i) {
+                    const int mt = row_tile(i);
+                    f32x4 acc[NNT];
+#pragma unroll
+                    for (int nt = 0; nt < NNT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int kt = 0; kt < KMAX; ++kt) {
+                        if (2 * kt <= mt) {
+#pragma unroll
+                            for (int nt = 0; nt < NNT; ++nt) acc[nt] = mfma16(t1[i][kt], bR[kt][nt], acc[nt]);
+                        }
+                    }
+#pragma unroll
+                    for (int nt = 0; nt < NNT; ++nt) st4(&Ue[(16 * nt + r16) * UP + 16 * mt + 4 * g], cvt4(acc[nt]));
+                }
+            }
+            fetch_t(nx);
+            __syncthreads();
+
+            // ---- interval 2: S^T += K^T U_eff, this wave's d_k rows; K^T comes out of the
+            // transposing read.  Done in groups of KG k-steps to bound the registers in flight.
+            {
+                constexpr int KG = NKT < 4 ? NKT : 4;
+#pragma unroll
+                for (int k0 = 0; k0 < NKT; k0 += KG) {
+                    bf16x8 b[KG][NNT], ak[KG][MPW];
+#pragma unroll
+                    for (int kk = 0; kk < KG; ++kk) {
+                        const int kt = k0 + kk;
+#pragma unroll
+                        for (int nt = 0; nt < NNT; ++nt) b[kk][nt] = ld8(&Ue[(16 * nt + r16) * UP + 32 * kt + 8 * g]);
+#pragma unroll
+                        for (int a = 0; a < MPW; ++a) {
+                            const bf16 *p = &Kc[(32 * kt + 8 * g + (r16 >> 2)) * KP + 16 * (W * MPW + a) + 4 * (r16 & 3)];
+                            ak[kk][a] = join(lds_read_tr4(p), lds_read_tr4(p + 4 * KP));
+                        }
+                    }
+                    LDS_FENCE();
+#pragma unroll
+                    for (int kk = 0; kk < KG; ++kk)
+#pragma unroll
+                        for (int a = 0; a < MPW; ++a)
+#pragma unroll
+                            for (int nt = 0; nt < NNT; ++nt) sacc[a][nt] = mfma16(ak[kk][a], b[kk][nt], sacc[a][nt]);
                 }
             }
 #pragma unroll
-            for (int nt = 0; nt < NNT; ++nt) st4(&Ue[(16 * nt + r16) * UP + 16 * mt + 4 * g], cvt4(acc[nt]));
+            for (int a = 0; a < MPW; ++a)
+#pragma unroll
+                for (int nt = 0; nt < NNT; ++nt)
+                    st4(&Sb[(16 * nt + r16) * SP + 16 * (W * MPW + a) + 4 * g], cvt4(sacc[a][nt]));
+            if (!kDoubleK) __syncthreads();   // interval 3: the io waves overwrite K in place
+            __syncthreads();
         }
-        fetch_t(nx);
+
+        if (SL) {
+#pragma unroll
+            for (int a = 0; a < MPW; ++a)
+#pragma unroll
+                for (int nt = 0; nt < NNT; ++nt)
+                    *reinterpret_cast<f32x4 *>(SL + chain * (size_t)D * D + (size_t)(dv0 + 16 * nt + r16) * D +
+                                               16 * (W * MPW + a) + 4 * g) = sacc[a][nt];
+        }
+    };
+
+    // ------------------------------------------------------------------ io waves
+    auto io_wave = [&](auto Wc) {
+        constexpr int W = decltype(Wc)::value;
+        const int tb0 = lane0 + 64 * W;                            // thread index among the io waves
+        int tb = tb0, lane = lane0, r16 = lane & 15, g = lane >> 4;
+
+        constexpr int VPR = D / 8;                                 // 16-byte vectors per row of K / Q
+        constexpr int KV = (N * D / 8 + NTHR - 1) / NTHR;          // vectors of K per thread
+        constexpr int QV = (C * D / 8 + NTHR - 1) / NTHR;          // vectors of Q per thread
+        constexpr int PPR = TV / 8;                                // 16-byte pieces per row of the V tile
+        constexpr int VV = (N * PPR + NTHR - 1) / NTHR;            // vectors of the V tile per thread
+        constexpr int OV = (C * PPR + NTHR - 1) / NTHR;            // vectors of the O tile per thread
+        bf16x8 kreg[KV], qreg[QV], vreg[VV];
+        bf16 breg = (bf16)0.0f;
+        bf16x8 p2[T2][NKT];        // P tiles of this wave's token tiles (those the causal mask keeps)
+
+        // token tiles of O owned by this wave: W and (with 8 tiles) 7 - W
+        constexpr auto tok_tile = [](int i) constexpr { return CT >= 8 ? ((i & 1) ? 8 * (i >> 1) + 7 - W : 8 * (i >> 1) + W) : W + 4 * i; };
+        // causal readout: token tile tt sees virtual tokens < R (16 tt + 16)
+        constexpr auto ksteps_of = [](int tt) constexpr { return (R * (16 * tt + 16) + 31) / 32; };
+
+        // K moves in two halves (vectors [0, KH) and [KH, KV) of every thread) so that its
+        // staging and load issue can be spread over two intervals
+        constexpr int KH = KV / 2;
+        auto fetch_k = [&](size_t cid, int q0, int q1) {
+            const bf16 *Kg = K + cid * (size_t)N * D;
+#pragma unroll
+            for (int q = 0; q < KV; ++q) {
+                const int v = tb + NTHR * q;
+                if (q >= q0 && q < q1 && ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8)) kreg[q] = ld8(Kg + (size_t)v * 8);
+            }
+        };
+        auto fetch_vqb = [&](size_t cid) {
+            const bf16 *Vg = V + cid * (size_t)N * D + dv0;
+            const bf16 *Qg = Q + cid * (size_t)C * D;
+#pragma unroll
+            for (int q = 0; q < VV; ++q) {
+                int v = tb + NTHR * q;
+                v = v < N * PPR ? v : N * PPR - 1;                 // clamp instead of branching
+                vreg[q] = ld8(Vg + (size_t)(v / PPR) * D + (v % PPR) * 8);
+            }
+#pragma unroll
+            for (int q = 0; q < QV; ++q) {
+                const int v = tb + NTHR * q;
+                if ((q + 1) * NTHR <= C * D / 8 || v < C * D / 8) qreg[q] = ld8(Qg + (size_t)v * 8);
+            }
+            breg = beta[cid * (size_t)N + (tb % N)];
+        };
+        auto fetch_p = [&](size_t cid) {
+            const bf16 *Pc = Pt + cid * (size_t)C * N;
+#pragma unroll
+            for (int i = 0; i < T2; ++i) {
+                const int tt = tok_tile(i);
+#pragma unroll
+                for (int kt = 0; kt < NKT; ++kt)
+                    if (kt < ksteps_of(tt)) p2[i][kt] = ld8(Pc + ((size_t)(tt * NKT + kt) * 64 + lane) * 8);
+            }
+        };
+        auto stage_k = [&](bf16 *Kd, int q0, int q1) {
+#pragma unroll
+            for (int q = 0; q < KV; ++q) {
+                const int v = tb + NTHR * q;
+                if (q >= q0 && q < q1 && ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8))
+                    st8(&Kd[(v / VPR) * KP + (v % VPR) * 8], kreg[q]);
+            }
+        };
+        auto stage_vqb = [&]() {
+#pragma unroll
+            for (int q = 0; q < VV; ++q) {
+                const int v = tb + NTHR * q;
+                if (v < N * PPR) st8(&Vs[(v / PPR) * VP + (v % PPR) * 8], vreg[q]);
+            }
+#pragma unroll
+            for (int q = 0; q < QV; ++q) {
+                const int v = tb + NTHR * q;
+                if ((q + 1) * NTHR <= C * D / 8 || v < C * D / 8) st8(&Qs[(v / VPR) * KP + (v % VPR) * 8], qreg[q]);
+            }
+            if (tb < N) bs[tb] = (float)breg;
+        };
+        // the O tile of one chunk (chunk tokens x TV features), LDS -> its rows of O
+        auto copy_out = [&](size_t cid) {
+            bf16 *Oc = O + cid * (size_t)C * D;
+#pragma unroll
+            for (int q = 0; q < OV; ++q) {
+                const int v = tb + NTHR * q;
+                if ((q + 1) * NTHR <= C * PPR || v < C * PPR)
+                    st8(Oc + (size_t)(v / PPR) * D + dv0 + 8 * (v % PPR), ld8(&Ob[(v / PPR) * OP + 8 * (v % PPR)]));
+            }
+        };
+
+        if (NC > 0) {
+            fetch_k(c0, 0, KV);
+            fetch_vqb(c0);
+            fetch_p(c0);
+            stage_k(Ks, 0, KV);
+            stage_vqb();
+            const size_t c1 = NC > 1 ? c0 + 1 : c0;
+            fetch_k(c1, 0, KV);
+            fetch_vqb(c1);
+        }
         __syncthreads();
 
-        // ---- (2) O^T = S Q^T + U_eff^T P^T : token tiles dealt to the waves
-#pragma unroll
-        for (int i = 0; i < T2; ++i) {
-            const int tt = tok_tile(i);
-            f32x4 oacc[NNT];
-#pragma unroll
-            for (int md = 0; md < NNT; ++md) oacc[md] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) {
-                bf16x8 b = ld8(&Qs[(16 * tt + r16) * KP + 32 * ks + 8 * g]);
+        for (int ch = 0; ch < NC; ++ch) {
+            tb = tb0;
+            asm volatile("" : "+v"(tb));
+            lane = tb & 63; r16 = lane & 15; g = lane >> 4;
+            const size_t cid = c0 + ch;
+            const size_t n1 = ch + 1 < NC ? cid + 1 : cid;          // chunk held in registers
+            const size_t n2 = ch + 2 < NC ? cid + 2 : c0 + NC - 1;  // chunk to request next
+
+            // ---- interval 0: previous O tile out; O^T = S Q^T for this wave's token tiles; first
+            // half of the next chunk's K into the buffer this step does not read
+            if (ch > 0) copy_out(cid - 1);
+            f32x4 oacc[T2][NNT];
+            {
+                bf16x8 aS[NNT][NKS], bQ[T2][NKS];
 #pragma unroll
                 for (int md = 0; md < NNT; ++md)
-                    oacc[md] = mfma16(ld8(&Scur[(16 * md + r16) * SP + 32 * ks + 8 * g]), b, oacc[md]);
-            }
-            const int ksteps = (R * (16 * tt + 16) + 31) / 32;
 #pragma unroll
-            for (int kt = 0; kt < NKT; ++kt)
-                if (kt < ksteps) {
+                    for (int ks = 0; ks < NKS; ++ks) aS[md][ks] = ld8(&Sb[(16 * md + r16) * SP + 32 * ks + 8 * g]);
+#pragma unroll
+                for (int i = 0; i < T2; ++i)
+#pragma unroll
+                    for (int ks = 0; ks < NKS; ++ks) bQ[i][ks] = ld8(&Qs[(16 * tok_tile(i) + r16) * KP + 32 * ks + 8 * g]);
+                LDS_FENCE();
+#pragma unroll
+                for (int i = 0; i < T2; ++i) {
+#pragma unroll
+                    for (int md = 0; md < NNT; ++md) oacc[i][md] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+                        for (int md = 0; md < NNT; ++md) oacc[i][md] = mfma16(aS[md][ks], bQ[i][ks], oacc[i][md]);
+                }
+            }
+            bf16 *Knext = Ks + (kDoubleK ? ((ch + 1) & 1) * N * KP : 0);
+            if (kDoubleK) {
+                stage_k(Knext, 0, KH);
+                fetch_k(n2, 0, KH);
+            }
+            __syncthreads();
+
+            // ---- interval 1: next chunk's V tile, Q, beta registers -> LDS, the chunk after it
+            // on its way
+            stage_vqb();
+            fetch_vqb(n2);
+            __syncthreads();
+
+            // ---- interval 2: O^T += U_eff^T P^T, O tile to LDS
+            {
+                constexpr int KMAX = ksteps_of(tok_tile(T2 - 1)) > ksteps_of(tok_tile(0)) ? ksteps_of(tok_tile(T2 - 1))
+                                                                                          : ksteps_of(tok_tile(0));
+                constexpr int KM = KMAX < NKT ? KMAX : NKT;
+                bf16x8 aU[KM][NNT];
+#pragma unroll
+                for (int kt = 0; kt < KM; ++kt)
 #pragma unroll
                     for (int md = 0; md < NNT; ++md)
-                        oacc[md] = mfma16(join(ld4(&Ue[(16 * md + r16) * UP + 32 * kt + 4 * g]),
-                                               ld4(&Ue[(16 * md + r16) * UP + 32 * kt + 16 + 4 * g])),
-                                          p2[i][kt], oacc[md]);
+                        aU[kt][md] = join(ld4(&Ue[(16 * md + r16) * UP + 32 * kt + 4 * g]),
+                                          ld4(&Ue[(16 * md + r16) * UP + 32 * kt + 16 + 4 * g]));
+                LDS_FENCE();
+#pragma unroll
+                for (int i = 0; i < T2; ++i) {
+                    const int tt = tok_tile(i);
+#pragma unroll
+                    for (int kt = 0; kt < KM; ++kt)
+                        if (kt < ksteps_of(tt)) {
+#pragma unroll
+                            for (int md = 0; md < NNT; ++md) oacc[i][md] = mfma16(aU[kt][md], p2[i][kt], oacc[i][md]);
+                        }
+#pragma unroll
+                    for (int md = 0; md < NNT; ++md)
+                        st4(&Ob[(16 * tt + r16) * OP + 16 * md + 4 * g], cvt4(oacc[i][md]));
                 }
-#pragma unroll
-            for (int md = 0; md < NNT; ++md) {
-                if (kWriter) st4(&Ocur[(16 * tt + r16) * OP + 16 * md + 4 * g], cvt4(oacc[md]));
-                else st4(Oc + (size_t)(16 * tt + r16) * D + dv0 + 16 * md + 4 * g, cvt4(oacc[md]));
             }
-        }
-        fetch_p(nx);
-
-        // ---- (3) S^T += K^T U_eff : this wave's d_k rows; K^T comes out of the transposing read
-#pragma unroll
-        for (int kt = 0; kt < NKT; ++kt) {
-            bf16x8 b[NNT];
-#pragma unroll
-            for (int nt = 0; nt < NNT; ++nt) b[nt] = ld8(&Ue[(16 * nt + r16) * UP + 32 * kt + 8 * g]);
-#pragma unroll
-            for (int a = 0; a < MPW; ++a) {
-                const bf16 *p = &Ks[(32 * kt + 8 * g + (r16 >> 2)) * KP + 16 * (w * MPW + a) + 4 * (r16 & 3)];
-                bf16x8 ak = join(lds_read_tr4(p), lds_read_tr4(p + 4 * KP));
-#pragma unroll
-                for (int nt = 0; nt < NNT; ++nt) sacc[a][nt] = mfma16(ak, b[nt], sacc[a][nt]);
+            fetch_p(n1);
+            if (kDoubleK) {
+                stage_k(Knext, KH, KV);
+                fetch_k(n2, KH, KV);
+            } else {
+                // ---- interval 3: K of the next chunk replaces this chunk's in place
+                __syncthreads();
+                stage_k(Ks, 0, KV);
+                fetch_k(n2, 0, KV);
             }
+            __syncthreads();
         }
-        bf16 *Snext = Sb + (cur ^ 1) * TV * SP;
-#pragma unroll
-        for (int a = 0; a < MPW; ++a)
-#pragma unroll
-            for (int nt = 0; nt < NNT; ++nt)
-                st4(&Snext[(16 * nt + r16) * SP + 16 * (w * MPW + a) + 4 * g], cvt4(sacc[a][nt]));
-        __syncthreads();
-    }
+        if (NC > 0) copy_out(c0 + NC - 1);
+    };
 
-    if (SL) {
-#pragma unroll
-        for (int a = 0; a < MPW; ++a)
-#pragma unroll
-            for (int nt = 0; nt < NNT; ++nt)
-                *reinterpret_cast<f32x4 *>(SL + chain * (size_t)D * D + (size_t)(dv0 + 16 * nt + r16) * D +
-                                           16 * (w * MPW + a) + 4 * g) = sacc[a][nt];
+    switch (wave) {
+    case 0: state_wave(std::integral_constant<int, 0>{}); break;
+    case 1: state_wave(std::integral_constant<int, 1>{}); break;
+    case 2: state_wave(std::integral_constant<int, 2>{}); break;
+    case 3: state_wave(std::integral_constant<int, 3>{}); break;
+    case 4: io_wave(std::integral_constant<int, 0>{}); break;
+    case 5: io_wave(std::integral_constant<int, 1>{}); break;
+    case 6: io_wave(std::integral_constant<int, 2>{}); break;
+    default: io_wave(std::integral_constant<int, 3>{}); break;
     }
 }
 
@@ -379,11 +504,19 @@ static hipError_t launch_scan_instance(const void *Q, const void *K, const void 
     auto kern = scan_kernel<D, N, C, TV>;
     constexpr size_t lds = ScanLds<D, N, C, TV>::total;
     static_assert(lds <= kMaxLdsBytes, "scan kernel LDS plan exceeds the CU");
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    // the LDS opt-in is per device and sticks: ask once per device, not once per launch
+    static int armed_device = -1;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
+    if (armed_device != dev) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        armed_device = dev;
+    }
     const unsigned grid = (unsigned)heads * (D / TV);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(scan_threads<N>()), lds, stream, (const bf16 *)Q,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kScanThreads), lds, stream, (const bf16 *)Q,
                        (const bf16 *)K, (const bf16 *)V, (const bf16 *)beta, (const bf16 *)Tt,
                        (const bf16 *)Pt, S0, (bf16 *)O, SL, heads, NC);
     return hipGetLastError();

@@ -41,6 +41,22 @@ def test_version_and_status_strings(pf):
     assert pf.pf_status_str(99) == "unknown status"
 
 
+def test_flow_block(pf):
+    F32, BF = pf.PF_F32, pf.PF_BF16
+    assert pf.pf_delta_fwd_block(128, 128, 2, 64, BF) == 64
+    assert pf.pf_delta_fwd_block(128, 128, 2, 128, BF) == 128
+    assert pf.pf_delta_fwd_block(128, 128, 4, 128, BF) == 64            # 512 virtual tokens -> 2 x 256
+    assert pf.pf_delta_fwd_block(64, 64, 1, 512, BF) == 128
+    assert pf.pf_delta_fwd_block(16, 16, 1, 16, F32) == 0
+    assert pf.pf_delta_fwd_block(128, 128, 8, 64, BF) == 0
+    # workspace follows the block, not the requested chunk
+    assert (pf.pf_delta_fwd_workspace_bytes(2, 16, 8192, 128, 128, 4, 128, BF)
+            == pf.pf_delta_fwd_workspace_bytes(2, 16, 8192, 128, 128, 4, 64, BF))
+    # the split entry points only take the block itself
+    fake = 0x1000
+    assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 256, 128, 128, 4, 128, 0) == pf.PF_ERR_UNSUPPORTED
+
+
 def test_supported_families(pf):
     BF, F32 = pf.PF_BF16, pf.PF_F32
     assert pf.pf_delta_fwd_supported(16, 16, 1, 16, F32) == 1          # config 0
@@ -48,6 +64,8 @@ def test_supported_families(pf):
     assert pf.pf_delta_fwd_supported(128, 128, 2, 64, BF) == 2         # config 2
     assert pf.pf_delta_fwd_supported(128, 128, 4, 64, BF) == 2         # config 3, chunk 64
     assert pf.pf_delta_fwd_supported(128, 128, 2, 128, BF) == 2        # config 4
+    assert pf.pf_delta_fwd_supported(128, 128, 4, 128, BF) == 2        # config 3, chunk 128: two blocks of 64
+    assert pf.pf_delta_fwd_supported(128, 128, 8, 64, BF) == 0         # 512 virtual tokens, no smaller block
     assert pf.pf_delta_fwd_supported(128, 128, 2, 64, F32) == 0        # fp32 at that size: no LDS room
     assert pf.pf_delta_fwd_supported(20, 12, 3, 8, BF) == 1            # odd shape -> generic
     assert pf.pf_delta_fwd_supported(0, 16, 1, 16, F32) == 0

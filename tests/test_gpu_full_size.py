@@ -23,6 +23,7 @@ def pf():
     ("cfg1", [0, 13, 31]),
     ("cfg2", [0, 21, 63]),
     ("cfg3a", [0, 17]),
+    ("cfg3b", [3, 29]),
     ("cfg4", [5, 30]),
 ])
 def test_full_size_sampled_heads(pf, oracle, name, sample):
