@@ -110,6 +110,30 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
                        void *workspace, size_t workspace_bytes, pf_stream stream);
 
 /*
+ * The same chunked forward for general low-rank drivers (Section 3.1, before the delta mapping
+ * of its Remark): per (b, h), with A_t, B_t in R^{d_k x r} and Atil_t in R^{d_v x r} stored by
+ * column,
+ *
+ *   S_t = S_{t-1} + S_{t-1} A_t B_t^T + Atil_t B_t^T ,     o_t = S_t q_t .
+ *
+ *   Q     [B, H, L, d_k]      dt     in
+ *   A     [B, H, L, r, d_k]   dt     in   column j of A_t is A[b, h, t, j, :]
+ *   Atil  [B, H, L, r, d_v]   dt     in
+ *   Bm    [B, H, L, r, d_k]   dt     in
+ *   S0, O, S_L, stream               as for pf_delta_fwd
+ *
+ * The delta rule is the special case A = beta k, Atil = -beta v, B = -k.  Served by the generic
+ * kernel family only (pf_flow_fwd_supported tells whether the chunk's working set fits LDS);
+ * needs no workspace; L need not be a multiple of chunk; L == 0 is valid as for pf_delta_fwd.
+ * Same error behaviour as pf_delta_fwd.
+ */
+int pf_flow_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt);
+pf_status pf_flow_fwd(const void *Q, const void *A, const void *Atil, const void *Bm,
+                      const float *S0, void *O, float *S_L,
+                      int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt,
+                      pf_stream stream);
+
+/*
  * Step 2 of Section 3 on its own ("parallel compute": the flow of every chunk, no dependence
  * between chunks), MFMA path only and only for chunk == pf_delta_fwd_block(...) (else
  * PF_ERR_UNSUPPORTED).  With n = chunk * r,

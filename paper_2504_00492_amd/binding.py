@@ -14,7 +14,7 @@ PF_OK, PF_ERR_NULL, PF_ERR_SHAPE, PF_ERR_UNSUPPORTED, PF_ERR_ALIGN, PF_ERR_WORKS
 PF_F32, PF_BF16 = 0, 1
 
 EXPORTS = ["pf_version", "pf_status_str", "pf_delta_fwd_supported", "pf_delta_fwd_block", "pf_delta_fwd_workspace_bytes",
-           "pf_delta_fwd", "pf_delta_chunk_flow", "pf_delta_chunk_scan"]
+           "pf_delta_fwd", "pf_flow_fwd_supported", "pf_flow_fwd", "pf_delta_chunk_flow", "pf_delta_chunk_scan"]
 
 
 class PfError(RuntimeError):
@@ -41,6 +41,10 @@ def _load() -> ctypes.CDLL:
     lib.pf_delta_fwd_workspace_bytes.argtypes = [i] * 8
     lib.pf_delta_fwd.restype = i
     lib.pf_delta_fwd.argtypes = [vp] * 7 + [i] * 8 + [vp, sz, vp]
+    lib.pf_flow_fwd_supported.restype = i
+    lib.pf_flow_fwd_supported.argtypes = [i, i, i, i, i]
+    lib.pf_flow_fwd.restype = i
+    lib.pf_flow_fwd.argtypes = [vp] * 7 + [i] * 8 + [vp]
     lib.pf_delta_chunk_flow.restype = i
     lib.pf_delta_chunk_flow.argtypes = [vp] * 5 + [i] * 7 + [vp]
     lib.pf_delta_chunk_scan.restype = i
@@ -97,6 +101,16 @@ def pf_delta_fwd(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, wor
                                  _stream_handle(stream)))
 
 
+def pf_flow_fwd_supported(d_k, d_v, r, chunk, dt) -> int:
+    return int(_lib.pf_flow_fwd_supported(d_k, d_v, r, chunk, dt))
+
+
+def pf_flow_fwd(Q, A, Atil, Bm, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, stream=None) -> int:
+    """Raw call; returns the pf_status.  Pointers may be torch tensors, ints or None."""
+    return int(_lib.pf_flow_fwd(_ptr(Q), _ptr(A), _ptr(Atil), _ptr(Bm), _ptr(S0), _ptr(O), _ptr(S_L),
+                                B, H, L, d_k, d_v, r, chunk, dt, _stream_handle(stream)))
+
+
 def pf_delta_chunk_flow(Q, K, beta, Tt, Pt, B, H, L, d_k, d_v, r, chunk, stream=None) -> int:
     return int(_lib.pf_delta_chunk_flow(_ptr(Q), _ptr(K), _ptr(beta), _ptr(Tt), _ptr(Pt),
                                         B, H, L, d_k, d_v, r, chunk, _stream_handle(stream)))
@@ -143,4 +157,38 @@ def delta_fwd(Q, K, V, beta, S0=None, *, chunk: int, workspace=None, stream=None
     st = pf_delta_fwd(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, workspace, wbytes, stream)
     if st != PF_OK:
         raise PfError(st, "pf_delta_fwd")
+    return O, S_L
+
+
+def flow_fwd(Q, A, Atil, Bm, S0=None, *, chunk: int, stream=None):
+    """Convenience wrapper over pf_flow_fwd (general drivers of Section 3.1) for torch CUDA tensors.
+
+    Q [B,H,L,dk], A [B,H,L,r,dk], Atil [B,H,L,r,dv], Bm [B,H,L,r,dk] (float32 or bfloat16,
+    contiguous), S0 [B,H,dv,dk] float32 or None.  Allocates O and S_L with torch, then makes
+    exactly one library call.  Returns (O, S_L)."""
+    import torch
+    for t in (Q, A, Atil, Bm):
+        if not t.is_cuda:
+            raise ValueError("flow_fwd needs CUDA (HIP) tensors; there is no CPU path")
+        if not t.is_contiguous():
+            raise ValueError("inputs must be contiguous")
+    B, H, L, r, d_k = A.shape
+    d_v = Atil.shape[-1]
+    if Q.dtype == torch.float32:
+        dt = PF_F32
+    elif Q.dtype == torch.bfloat16:
+        dt = PF_BF16
+    else:
+        raise ValueError("dtype must be float32 or bfloat16")
+    if not (A.dtype == Atil.dtype == Bm.dtype == Q.dtype):
+        raise ValueError("Q, A, Atil, Bm must share one dtype")
+    if Q.shape != (B, H, L, d_k) or Atil.shape != (B, H, L, r, d_v) or Bm.shape != (B, H, L, r, d_k):
+        raise ValueError("inconsistent shapes")
+    if S0 is not None and (S0.dtype != torch.float32 or S0.shape != (B, H, d_v, d_k) or not S0.is_contiguous()):
+        raise ValueError("S0 must be contiguous float32 [B,H,dv,dk]")
+    O = torch.empty((B, H, L, d_v), dtype=Q.dtype, device=Q.device)
+    S_L = torch.empty((B, H, d_v, d_k), dtype=torch.float32, device=Q.device)
+    st = pf_flow_fwd(Q, A, Atil, Bm, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, stream)
+    if st != PF_OK:
+        raise PfError(st, "pf_flow_fwd")
     return O, S_L

@@ -129,6 +129,30 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
     return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
 }
 
+int pf_flow_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt)
+{
+    if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return 0;
+    if (dt != PF_F32 && dt != PF_BF16) return 0;
+    if ((long long)chunk * r > 65536 || d_k > 65536 || d_v > 65536) return 0;
+    return pf::generic_lds_bytes(d_k, d_v, r, chunk) <= pf::kMaxLdsBytes ? 1 : 0;
+}
+
+pf_status pf_flow_fwd(const void *Q, const void *A, const void *Atil, const void *Bm, const float *S0,
+                      void *O, float *S_L, int B, int H, int L, int d_k, int d_v, int r, int chunk,
+                      pf_dtype dt, pf_stream stream)
+{
+    if (L != 0 && (!Q || !A || !Atil || !Bm || !O)) return PF_ERR_NULL;
+    pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
+    if (st != PF_OK) return st;
+    if (!pf_flow_fwd_supported(d_k, d_v, r, chunk, dt)) return PF_ERR_UNSUPPORTED;
+    if (!aligned16(Q) || !aligned16(A) || !aligned16(Atil) || !aligned16(Bm) || !aligned16(O) ||
+        !aligned16(S0) || !aligned16(S_L))
+        return PF_ERR_ALIGN;
+    hipError_t e = pf::launch_generic_drivers(Q, A, Atil, Bm, S0, O, S_L, B * H, L, d_k, d_v, r, chunk,
+                                              dt == PF_BF16, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+}
+
 pf_status pf_delta_chunk_flow(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,
                               int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_stream stream)
 {

@@ -10,6 +10,11 @@
 //   U_eff  = U' - W S^T                      (U + W S_0^T of Theorem 3.2)
 //   O      = Q S^T + (Mbar (.) Q K^T) U_eff   Mbar inclusive in time       (flow truncated at t)
 //   S     += U_eff^T K                       (S_1 of Theorem 3.2)
+//
+// The same kernel serves the general low-rank drivers of Section 3.1,
+//   S_t = S_{t-1} + S_{t-1} A_t B_t^T + Atil_t B_t^T,
+// by loading (K, beta K, beta V) := (-B, A, -Atil): Theorem 3.2's Id - M (.) A B^T is then
+// Id + M (.) (A)(-B)^T, its U + W S_0^T is -(U_eff), and every later line is unchanged.
 #include "pf_internal.h"
 #include "pf_common.cuh"
 
@@ -51,7 +56,9 @@ __host__ __device__ inline GenericPlan generic_plan(int dk, int dv, int r, int c
     return p;
 }
 
-template <typename T>
+// kDrivers == false: (K, V, beta) are keys, values, betas of the delta rule.
+// kDrivers == true:  (K, V, beta) are (B, Atil, A) of the general recurrence (beta: [.., r, d_k]).
+template <typename T, bool kDrivers>
 __global__ __launch_bounds__(256) void generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                       const T *__restrict__ V, const T *__restrict__ beta,
                                                       const float *S0, T *__restrict__ O, float *SL,
@@ -67,7 +74,7 @@ __global__ __launch_bounds__(256) void generic_kernel(const T *__restrict__ Q, c
     const T *Qh = Q + head * (size_t)L * dk;
     const T *Kh = K + head * (size_t)L * r * dk;
     const T *Vh = V + head * (size_t)L * r * dv;
-    const T *bh = beta + head * (size_t)L * r;
+    const T *bh = beta + head * (size_t)L * r * (kDrivers ? dk : 1);
     T *Oh = O + head * (size_t)L * dv;
 
     for (int i = tid; i < dv * dk; i += nth) {
@@ -83,28 +90,30 @@ __global__ __launch_bounds__(256) void generic_kernel(const T *__restrict__ Q, c
         for (int i = tid; i < n * dk; i += nth) {
             const int row = i / dk, x = i % dk;
             const float kv = load_as_f32(Kh, ((size_t)c0 * r + row) * dk + x);
-            const float b = load_as_f32(bh, (size_t)c0 * r + row);
-            Kc[row * ldk + x] = kv;
-            Wc[row * ldk + x] = b * kv;
+            if (kDrivers) {
+                Kc[row * ldk + x] = -kv;
+                Wc[row * ldk + x] = load_as_f32(bh, ((size_t)c0 * r + row) * dk + x);
+            } else {
+                Kc[row * ldk + x] = kv;
+                Wc[row * ldk + x] = load_as_f32(bh, (size_t)c0 * r + row) * kv;
+            }
         }
         for (int i = tid; i < n * dv; i += nth) {
             const int row = i / dv, m = i % dv;
-            const float b = load_as_f32(bh, (size_t)c0 * r + row);
-            Uc[row * ldv + m] = b * load_as_f32(Vh, ((size_t)c0 * r + row) * dv + m);
+            const float vv = load_as_f32(Vh, ((size_t)c0 * r + row) * dv + m);
+            Uc[row * ldv + m] = kDrivers ? -vv : load_as_f32(bh, (size_t)c0 * r + row) * vv;
         }
         for (int i = tid; i < cl * dk; i += nth) {
             const int t = i / dk, x = i % dk;
             Qc[t * ldk + x] = load_as_f32(Qh, ((size_t)c0 + t) * dk + x);
         }
         __syncthreads();
-        // ---- G = M (.) diag(beta) K K^T  and  P = Mbar (.) Q K^T
+        // ---- G = M (.) (beta K) K^T  and  P = Mbar (.) Q K^T   (W still holds beta K here)
         for (int i = tid; i < n * n; i += nth) {
             const int row = i / n, col = i % n;
             float acc = 0.0f;
-            if (col / r < row / r) {
-                for (int x = 0; x < dk; ++x) acc = fmaf(Kc[row * ldk + x], Kc[col * ldk + x], acc);
-                acc *= load_as_f32(bh, (size_t)c0 * r + row);
-            }
+            if (col / r < row / r)
+                for (int x = 0; x < dk; ++x) acc = fmaf(Wc[row * ldk + x], Kc[col * ldk + x], acc);
             G[row * ldn + col] = acc;
         }
         for (int i = tid; i < cl * n; i += nth) {
@@ -167,29 +176,35 @@ size_t generic_lds_bytes(int dk, int dv, int r, int chunk)
     return generic_plan(dk, dv, r, chunk).total * sizeof(float);
 }
 
+template <typename T, bool kDrivers>
+static hipError_t launch_generic_instance(const void *Q, const void *K, const void *V, const void *beta,
+                                          const float *S0, void *O, float *SL, int heads, int L, int dk, int dv,
+                                          int r, int chunk, hipStream_t stream)
+{
+    const size_t lds = generic_lds_bytes(dk, dv, r, chunk);
+    auto kern = generic_kernel<T, kDrivers>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(heads), dim3(256), lds, stream, (const T *)Q, (const T *)K, (const T *)V,
+                       (const T *)beta, S0, (T *)O, SL, L, dk, dv, r, chunk);
+    return hipGetLastError();
+}
+
 hipError_t launch_generic(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
                           void *O, float *SL, int heads, int L, int dk, int dv, int r, int chunk,
                           bool is_bf16, hipStream_t stream)
 {
-    const size_t lds = generic_lds_bytes(dk, dv, r, chunk);
-    hipError_t e;
-    if (is_bf16) {
-        auto kern = generic_kernel<uint16_t>;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, dim3(heads), dim3(256), lds, stream, (const uint16_t *)Q,
-                           (const uint16_t *)K, (const uint16_t *)V, (const uint16_t *)beta, S0,
-                           (uint16_t *)O, SL, L, dk, dv, r, chunk);
-    } else {
-        auto kern = generic_kernel<float>;
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kern, dim3(heads), dim3(256), lds, stream, (const float *)Q, (const float *)K,
-                           (const float *)V, (const float *)beta, S0, (float *)O, SL, L, dk, dv, r, chunk);
-    }
-    return hipGetLastError();
+    return is_bf16 ? launch_generic_instance<uint16_t, false>(Q, K, V, beta, S0, O, SL, heads, L, dk, dv, r, chunk, stream)
+                   : launch_generic_instance<float, false>(Q, K, V, beta, S0, O, SL, heads, L, dk, dv, r, chunk, stream);
+}
+
+hipError_t launch_generic_drivers(const void *Q, const void *A, const void *Atil, const void *Bm, const float *S0,
+                                  void *O, float *SL, int heads, int L, int dk, int dv, int r, int chunk,
+                                  bool is_bf16, hipStream_t stream)
+{
+    return is_bf16 ? launch_generic_instance<uint16_t, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, stream)
+                   : launch_generic_instance<float, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, stream);
 }
 
 }  // namespace pf

@@ -15,6 +15,10 @@ size_t generic_lds_bytes(int dk, int dv, int r, int chunk);
 hipError_t launch_generic(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
                           void *O, float *SL, int heads, int L, int dk, int dv, int r, int chunk,
                           bool is_bf16, hipStream_t stream);
+// general drivers (A, Atil, B) of Section 3.1 through the same kernel
+hipError_t launch_generic_drivers(const void *Q, const void *A, const void *Atil, const void *Bm,
+                                  const float *S0, void *O, float *SL, int heads, int L, int dk, int dv,
+                                  int r, int chunk, bool is_bf16, hipStream_t stream);
 
 // ---- MFMA path (pf_flow.hip, pf_scan.hip); d = d_k = d_v, n = chunk * r
 bool mfma_instance_exists(int d, int n, int chunk);

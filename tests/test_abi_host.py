@@ -123,6 +123,28 @@ def test_argument_checks_return_before_launch(pf):
     assert scan(A, A, A, A, A, A, A, A, A + 4, 1, 1, 128, 128, 128, 2, 64, 0) == pf.PF_ERR_ALIGN
 
 
+def test_general_driver_entry_checks(pf):
+    A = 0x10000
+    F32, BF = pf.PF_F32, pf.PF_BF16
+    assert pf.pf_flow_fwd_supported(16, 16, 1, 16, F32) == 1
+    assert pf.pf_flow_fwd_supported(20, 12, 3, 8, BF) == 1
+    assert pf.pf_flow_fwd_supported(128, 128, 2, 64, BF) == 0          # working set beyond 160 KiB of LDS
+    assert pf.pf_flow_fwd_supported(16, 16, 1, 16, 9) == 0
+    call = lambda Q=A, Ad=A, At=A, Bm=A, S0=A, O=A, SL=A, L=40, dk=16, dv=12, r=2, C=8, dt=F32: \
+        pf.pf_flow_fwd(Q, Ad, At, Bm, S0, O, SL, 1, 2, L, dk, dv, r, C, dt, 0)
+    assert call(Q=None) == pf.PF_ERR_NULL
+    assert call(Ad=None) == pf.PF_ERR_NULL
+    assert call(At=None) == pf.PF_ERR_NULL
+    assert call(Bm=None) == pf.PF_ERR_NULL
+    assert call(O=None) == pf.PF_ERR_NULL
+    assert call(L=-3) == pf.PF_ERR_SHAPE
+    assert call(r=0) == pf.PF_ERR_SHAPE
+    assert call(dk=128, dv=128, C=64) == pf.PF_ERR_UNSUPPORTED
+    assert call(dt=4) == pf.PF_ERR_UNSUPPORTED
+    assert call(Bm=A + 6) == pf.PF_ERR_ALIGN
+    assert call(S0=A + 4) == pf.PF_ERR_ALIGN
+
+
 def test_inputs_are_seeded_and_bf16_exact():
     import numpy as np
     from paper_2504_00492_amd import synth

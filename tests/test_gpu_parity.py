@@ -192,3 +192,52 @@ def test_mfma_in_place_state_split_sequence_and_determinism(pf, oracle):
         assert st == pf.PF_OK
     torch.cuda.synchronize()
     assert torch.equal(torch.cat([Oa, Ob], dim=2), O1) and torch.equal(S, S1)
+
+
+# ---------------------------------------------------------------- general drivers (Section 3.1)
+@pytest.mark.parametrize("kw", [
+    dict(L=48, r=1, dk=16, dv=16, C=16, dtype="f32"),
+    dict(L=45, r=2, dk=20, dv=12, C=8, dtype="f32"),      # ragged tail, d_k != d_v
+    dict(L=64, r=3, dk=24, dv=40, C=16, dtype="bf16"),
+])
+def test_general_driver_entry(pf, oracle, kw):
+    """pf_flow_fwd against the oracle's general-driver recurrence: drivers that are NOT of delta
+    form (A, Atil, B independent), non-symmetric S0, two heads."""
+    import torch
+    L, r, dk, dv, C = kw["L"], kw["r"], kw["dk"], kw["dv"], kw["C"]
+    _say(f"general drivers {kw}")
+    rng = np.random.default_rng(77)
+    N = 2
+    A = (0.3 * rng.standard_normal((N, L, r, dk))).astype(np.float32)
+    At = rng.standard_normal((N, L, r, dv)).astype(np.float32)
+    Bm = (rng.standard_normal((N, L, r, dk)) / np.sqrt(dk)).astype(np.float32)
+    Q = rng.standard_normal((N, L, dk)).astype(np.float32)
+    S0 = rng.standard_normal((N, dv, dk)).astype(np.float32)
+    tdt = torch.float32 if kw["dtype"] == "f32" else torch.bfloat16
+    dev = torch.device("cuda:0")
+    up = lambda a: torch.from_numpy(a).to(dev).to(tdt).reshape((1, N) + a.shape[1:]).contiguous()
+    tq, ta, tat, tb = up(Q), up(A), up(At), up(Bm)
+    ts0 = torch.from_numpy(S0).to(dev).reshape(1, N, dv, dk).contiguous()
+    O, SL = pf.flow_fwd(tq, ta, tat, tb, ts0, chunk=C)
+    torch.cuda.synchronize()
+    O = O.float().cpu().numpy()[0]
+    SL = SL.cpu().numpy()[0]
+    back = lambda t: t.float().cpu().numpy()[0].astype(np.float64)      # the values the GPU saw
+    tol = 1e-4 if kw["dtype"] == "f32" else 2e-2
+    for h in range(N):
+        Oref, SLref = oracle.flow_head(back(ta)[h], back(tat)[h], back(tb)[h], back(tq)[h], S0[h].astype(np.float64))
+        eO, eS = rel_l2(O[h], Oref), rel_l2(SL[h], SLref)
+        _say(f"    head {h}: relL2(O)={eO:.3e} relL2(S_L)={eS:.3e}")
+        assert eO <= tol and eS <= tol
+    # the delta mapping through this entry equals pf_delta_fwd
+    K = rng.standard_normal((N, L, r, dk)).astype(np.float32)
+    K /= np.linalg.norm(K, axis=-1, keepdims=True)
+    V = rng.standard_normal((N, L, r, dv)).astype(np.float32)
+    beta = rng.uniform(0, 1, (N, L, r)).astype(np.float32)
+    if kw["dtype"] == "f32":
+        tk, tv, tbeta = up(K), up(V), up(beta)
+        O1, S1 = pf.delta_fwd(tq, tk, tv, tbeta, ts0, chunk=C)
+        O2, S2 = pf.flow_fwd(tq, tbeta[..., None] * tk, -(tbeta[..., None] * tv), -tk, ts0, chunk=C)
+        torch.cuda.synchronize()
+        assert rel_l2(O2.cpu().numpy(), O1.cpu().numpy()) <= 1e-5
+        assert rel_l2(S2.cpu().numpy(), S1.cpu().numpy()) <= 1e-5
