@@ -12,14 +12,17 @@
 // Only R -> U_eff -> S_c+1 is a chain from one chunk to the next; the readout O_c hangs off it.
 // The workgroup therefore has two kinds of wavefronts, one of each per SIMD:
 //
-//   state waves (0..3)  run the chain and nothing else: R (interval 0), U_eff (interval 1),
-//                       S update (interval 2).  Their only global loads are their own T tiles,
-//                       straight into MFMA operand registers, one chunk ahead.
-//   io waves (4..7)     do everything that can be late or early: Q S^T (interval 0), staging of
-//                       the next chunk's K, V tile, Q, beta from registers into LDS and the
-//                       loads of the chunk after it (interval 1), U_eff^T P^T and the O tile
-//                       (interval 2), and the coalesced copy of the previous O tile to global
-//                       memory.  Their load-issue stalls and LDS stores overlap the chain.
+//   state waves (0..3)  run the chain: R (interval 0), U_eff (interval 1), S update (interval 2).
+//                       Their global loads are their own T tiles, straight into MFMA operand
+//                       registers, one chunk ahead.  For n <= 128 they also compute O: S and
+//                       U_eff are already in their registers as operands of the chain, so
+//                       Q S^T and U_eff^T P^T cost them no LDS reads but Q.
+//   io waves (4..7)     do everything that can be late or early: staging of the next chunk's K,
+//                       V tile, Q, beta from registers into LDS and the loads of the chunk after
+//                       it (spread over the intervals), the coalesced copy of the previous O tile
+//                       to global memory, and for n = 256 (where the state waves have no
+//                       registers to spare) Q S^T (interval 0) and U_eff^T P^T (interval 2).
+//                       Their load-issue stalls and LDS stores overlap the chain.
 //
 // S^T lives in fp32 accumulators of the state waves (wave w owns d_k rows [w d/4, (w+1) d/4)); a
 // bf16 copy in LDS ([d_v][d_k]) feeds the MFMA operands of the next chunk.  K is read from LDS
@@ -92,6 +95,9 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     constexpr int KP = Ld::KP, VP = Ld::VP, SP = Ld::SP, UP = Ld::UP, OP = Ld::OP;
     constexpr int NTHR = kScanRoleThreads;
     constexpr bool kDoubleK = Ld::kDoubleK;
+    // Who computes O: the state waves when their register budget allows (they already hold S and
+    // U_eff as operands, so it costs them no LDS reads but Q), else the io waves.
+    constexpr bool kStateReadout = N <= 128;
     static_assert(D % 64 == 0 && TV % 16 == 0 && N % 32 == 0, "tile shapes");
     static_assert(MT % 4 == 0 && CT % 4 == 0, "every wave of a role owns the same number of tiles");
     static_assert(N <= NTHR, "beta of a chunk is fetched by one pass");
@@ -138,6 +144,22 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 st4(&Sb[(16 * nt + r16) * SP + 16 * mt + 4 * g], cvt4(v));
             }
 
+        // readout by the state waves (kStateReadout): token tiles of O owned by this wave, W and
+        // (with 8 tiles) 7 - W; token tile tt sees virtual tokens < R (16 tt + 16)
+        constexpr auto tok_tile = [](int i) constexpr { return CT >= 8 ? ((i & 1) ? 8 * (i >> 1) + 7 - W : 8 * (i >> 1) + W) : W + 4 * i; };
+        constexpr auto ksteps_of = [](int tt) constexpr { return (R * (16 * tt + 16) + 31) / 32; };
+        bf16x8 p2[T2][NKT];        // P tiles of this wave's token tiles (those the causal mask keeps)
+        auto fetch_p = [&](size_t cid) {
+            const bf16 *Pc = Pt + cid * (size_t)C * N;
+#pragma unroll
+            for (int i = 0; i < T2; ++i) {
+                const int tt = tok_tile(i);
+#pragma unroll
+                for (int kt = 0; kt < NKT; ++kt)
+                    if (kt < ksteps_of(tt)) p2[i][kt] = ld8(Pc + ((size_t)(tt * NKT + kt) * 64 + lane) * 8);
+            }
+        };
+
         bf16x8 t1[M1][NKT];        // T tiles of this wave's rows of U_eff (those below the diagonal)
         auto fetch_t = [&](size_t cid) {
             const bf16 *Tc = Tt + cid * (size_t)N * N;
@@ -149,7 +171,10 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                     if (2 * kt <= mt) t1[i][kt] = ld8(Tc + ((size_t)(mt * NKT + kt) * 64 + lane) * 8);
             }
         };
-        if (NC > 0) fetch_t(c0);
+        if (NC > 0) {
+            fetch_t(c0);
+            if constexpr (kStateReadout) fetch_p(c0);
+        }
         __syncthreads();
 
         for (int ch = 0; ch < NC; ++ch) {
@@ -168,8 +193,9 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             // read latency is paid once per interval instead of once per MFMA.
 
             // ---- interval 0: R = beta (.) (V - K S^T), rows (virtual tokens) dealt to the waves
+            f32x4 oacc[T2][NNT];
             {
-                bf16x8 bS[NNT][NKS], aK[M1][NKS];
+                bf16x8 bS[NNT][NKS], aK[M1][NKS], bQ[T2][NKS];
                 bf16x4 vt[M1][NNT];
                 f32x4 bt[M1];
 #pragma unroll
@@ -189,6 +215,13 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                     for (int nt = 0; nt < NNT; ++nt)
                         vt[i][nt] = lds_read_tr4(&Vs[(16 * mt + 4 * g + (r16 >> 2)) * VP + 16 * nt + 4 * (r16 & 3)]);
                 }
+                if constexpr (kStateReadout) {
+#pragma unroll
+                    for (int i = 0; i < T2; ++i)
+#pragma unroll
+                        for (int ks = 0; ks < NKS; ++ks)
+                            bQ[i][ks] = ld8(&Qs[(16 * tok_tile(i) + r16) * KP + 32 * ks + 8 * g]);
+                }
                 LDS_FENCE();
 #pragma unroll
                 for (int i = 0; i < M1; ++i) {
@@ -204,6 +237,19 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                     for (int nt = 0; nt < NNT; ++nt) {
                         f32x4 rr = (__builtin_convertvector(vt[i][nt], f32x4) - acc[nt]) * bt[i];
                         st4(&Rs[(16 * nt + r16) * UP + 16 * mt + 4 * g], cvt4(rr));
+                    }
+                }
+                if constexpr (kStateReadout) {
+                    // O^T = S Q^T for this wave's token tiles: the rows of S just read as the B
+                    // operand of K S^T are, lane for lane, the A operand here
+#pragma unroll
+                    for (int i = 0; i < T2; ++i) {
+#pragma unroll
+                        for (int md = 0; md < NNT; ++md) oacc[i][md] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+                            for (int md = 0; md < NNT; ++md) oacc[i][md] = mfma16(bS[md][ks], bQ[i][ks], oacc[i][md]);
                     }
                 }
             }
@@ -237,7 +283,12 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                         }
                     }
 #pragma unroll
-                    for (int nt = 0; nt < NNT; ++nt) st4(&Ue[(16 * nt + r16) * UP + 16 * mt + 4 * g], cvt4(acc[nt]));
+                    // U_eff^T is stored with the tokens of every 32-block in the order two stacked
+                    // accumulator tiles have (position 8 g + e holds token 4 g + e for e < 4 and
+                    // 16 + 4 g + e - 4 for e >= 4): 16 consecutive bytes of a row are then one lane's
+                    // operand both for K^T U_eff (K^T read in the same order) and for U_eff^T P^T
+                    for (int nt = 0; nt < NNT; ++nt)
+                        st4(&Ue[(16 * nt + r16) * UP + 32 * (mt >> 1) + 8 * g + 4 * (mt & 1)], cvt4(acc[nt]));
                 }
             }
             fetch_t(nx);
@@ -257,8 +308,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                         for (int nt = 0; nt < NNT; ++nt) b[kk][nt] = ld8(&Ue[(16 * nt + r16) * UP + 32 * kt + 8 * g]);
 #pragma unroll
                         for (int a = 0; a < MPW; ++a) {
-                            const bf16 *p = &Kc[(32 * kt + 8 * g + (r16 >> 2)) * KP + 16 * (W * MPW + a) + 4 * (r16 & 3)];
-                            ak[kk][a] = join(lds_read_tr4(p), lds_read_tr4(p + 4 * KP));
+                            const bf16 *p = &Kc[(32 * kt + 4 * g + (r16 >> 2)) * KP + 16 * (W * MPW + a) + 4 * (r16 & 3)];
+                            ak[kk][a] = join(lds_read_tr4(p), lds_read_tr4(p + 16 * KP));
                         }
                     }
                     LDS_FENCE();
@@ -268,6 +319,18 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                         for (int a = 0; a < MPW; ++a)
 #pragma unroll
                             for (int nt = 0; nt < NNT; ++nt) sacc[a][nt] = mfma16(ak[kk][a], b[kk][nt], sacc[a][nt]);
+                    if constexpr (kStateReadout) {
+                        // O^T += U_eff^T P^T: the same U_eff registers, now as A operand
+#pragma unroll
+                        for (int kk = 0; kk < KG; ++kk)
+#pragma unroll
+                            for (int i = 0; i < T2; ++i)
+                                if (k0 + kk < ksteps_of(tok_tile(i))) {
+#pragma unroll
+                                    for (int md = 0; md < NNT; ++md)
+                                        oacc[i][md] = mfma16(b[kk][md], p2[i][k0 + kk], oacc[i][md]);
+                                }
+                    }
                 }
             }
 #pragma unroll
@@ -275,6 +338,14 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 #pragma unroll
                 for (int nt = 0; nt < NNT; ++nt)
                     st4(&Sb[(16 * nt + r16) * SP + 16 * (W * MPW + a) + 4 * g], cvt4(sacc[a][nt]));
+            if constexpr (kStateReadout) {
+#pragma unroll
+                for (int i = 0; i < T2; ++i)
+#pragma unroll
+                    for (int md = 0; md < NNT; ++md)
+                        st4(&Ob[(16 * tok_tile(i) + r16) * OP + 16 * md + 4 * g], cvt4(oacc[i][md]));
+                fetch_p(nx);
+            }
             if (!kDoubleK) __syncthreads();   // interval 3: the io waves overwrite K in place
             __syncthreads();
         }
@@ -382,7 +453,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         if (NC > 0) {
             fetch_k(c0, 0, KV);
             fetch_vqb(c0);
-            fetch_p(c0);
+            if constexpr (!kStateReadout) fetch_p(c0);
             stage_k(Ks, 0, KV);
             stage_vqb();
             const size_t c1 = NC > 1 ? c0 + 1 : c0;
@@ -403,7 +474,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             // half of the next chunk's K into the buffer this step does not read
             if (ch > 0) copy_out(cid - 1);
             f32x4 oacc[T2][NNT];
-            {
+            if constexpr (!kStateReadout) {
                 bf16x8 aS[NNT][NKS], bQ[T2][NKS];
 #pragma unroll
                 for (int md = 0; md < NNT; ++md)
@@ -438,7 +509,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             __syncthreads();
 
             // ---- interval 2: O^T += U_eff^T P^T, O tile to LDS
-            {
+            if constexpr (!kStateReadout) {
                 constexpr int KMAX = ksteps_of(tok_tile(T2 - 1)) > ksteps_of(tok_tile(0)) ? ksteps_of(tok_tile(T2 - 1))
                                                                                           : ksteps_of(tok_tile(0));
                 constexpr int KM = KMAX < NKT ? KMAX : NKT;
@@ -447,8 +518,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 for (int kt = 0; kt < KM; ++kt)
 #pragma unroll
                     for (int md = 0; md < NNT; ++md)
-                        aU[kt][md] = join(ld4(&Ue[(16 * md + r16) * UP + 32 * kt + 4 * g]),
-                                          ld4(&Ue[(16 * md + r16) * UP + 32 * kt + 16 + 4 * g]));
+                        aU[kt][md] = ld8(&Ue[(16 * md + r16) * UP + 32 * kt + 8 * g]);
                 LDS_FENCE();
 #pragma unroll
                 for (int i = 0; i < T2; ++i) {
@@ -464,7 +534,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                         st4(&Ob[(16 * tt + r16) * OP + 16 * md + 4 * g], cvt4(oacc[i][md]));
                 }
             }
-            fetch_p(n1);
+            if constexpr (!kStateReadout) fetch_p(n1);
             if (kDoubleK) {
                 stage_k(Knext, KH, KV);
                 fetch_k(n2, KH, KV);
