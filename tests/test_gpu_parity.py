@@ -241,3 +241,37 @@ def test_general_driver_entry(pf, oracle, kw):
         torch.cuda.synchronize()
         assert rel_l2(O2.cpu().numpy(), O1.cpu().numpy()) <= 1e-5
         assert rel_l2(S2.cpu().numpy(), S1.cpu().numpy()) <= 1e-5
+
+
+# ---------------------------------------------------------------- launch-shape edge cases
+def test_more_workgroups_than_the_gpu_holds(pf, oracle):
+    """640 heads x 4 d_v tiles = 2560 scan workgroups (ten per CU): workgroups are independent, so
+    a grid far beyond what is resident at once must give the same per-head results."""
+    w = synth.Workload("many", "bf16", 4, 160, 128, 64, 64, 1, 64, seed=41, s0_std=0.1)
+    _say(f"[case] many heads B={w.B} H={w.H} L={w.L} d={w.d_k} r={w.r} C={w.chunk}")
+    heads = [0, 1, 255, 256, 511, 639]
+    inp = synth.make_inputs(w)
+    dev = to_device(w, inp)
+    O, SL = run_gpu(pf, w, dev)
+    assert np.isfinite(O).all() and np.isfinite(SL).all()
+    sub = {k: (None if inp[k] is None else inp[k][heads]) for k in ("Q", "K", "V", "beta", "S0")}
+    Oref, SLref = oracle.delta_fwd(sub["Q"], sub["K"], sub["V"], sub["beta"], sub["S0"])
+    for i, h in enumerate(heads):
+        eO, eS = rel_l2(flat_heads(O)[h], Oref[i]), rel_l2(flat_heads(SL)[h], SLref[i])
+        _say(f"        head {h}: relL2(O)={eO:.3e} relL2(S_L)={eS:.3e}")
+        assert eO <= TOL["bf16"] and eS <= TOL["bf16"]
+
+
+def test_chunk_beyond_one_flow_block(pf, oracle):
+    """r = 4, chunk = 128 is 512 virtual tokens: it runs as flow blocks of 64 tokens
+    (pf_delta_fwd_block), against the oracle and bit-identical to chunk = 64."""
+    import torch
+    w = synth.WORKLOADS["cfg3b"].with_(B=1, H=3, L=512)
+    assert pf.pf_delta_fwd_block(w.d_k, w.d_v, w.r, w.chunk, pf.PF_BF16) == 64
+    _check(pf, oracle, w, expect_family=2)
+    inp = synth.make_inputs(w)
+    dev = to_device(w, inp)
+    O128, S128 = pf.delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], chunk=128)
+    O64, S64 = pf.delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], chunk=64)
+    torch.cuda.synchronize()
+    assert torch.equal(O128, O64) and torch.equal(S128, S64)
