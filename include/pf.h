@@ -64,8 +64,10 @@ const char *pf_status_str(pf_status s);
  *   1  generic path: one workgroup per (b, h), fp32 vector arithmetic, chunk state in LDS;
  *      any d_k, d_v, r, chunk whose per-chunk working set fits 160 KiB of LDS; both dtypes;
  *      L need not be a multiple of chunk (the tail is a shorter last chunk)
- *   2  MFMA path (PF_BF16 only): d_k = d_v in {64, 128}, L a multiple of chunk, and a flow
- *      block (see pf_delta_fwd_block) with block * r in {64, 128, 256}, block in {64, 128}
+ *   2  MFMA path (PF_BF16 only): d_k = d_v in {64, 128} and a flow block (see
+ *      pf_delta_fwd_block) with block * r in {64, 128, 256}, block in {64, 128}.  Any L: the
+ *      L % block tokens left over at the end of every (b, h) are taken by the generic kernel
+ *      from the state the whole blocks leave behind (the flows compose, Section 3.1).
  */
 int pf_delta_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt);
 
@@ -77,8 +79,8 @@ int pf_delta_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt);
  * is not 2.  Host only. */
 int pf_delta_fwd_block(int d_k, int d_v, int r, int chunk, pf_dtype dt);
 
-/* Bytes of device scratch pf_delta_fwd needs for these dimensions (0 for the generic path and
- * for unsupported dimensions).  Host only. */
+/* Bytes of device scratch pf_delta_fwd needs for these dimensions (0 for the generic path, for
+ * L shorter than one flow block and for unsupported dimensions).  Host only. */
 size_t pf_delta_fwd_workspace_bytes(int B, int H, int L, int d_k, int d_v, int r, int chunk,
                                     pf_dtype dt);
 

@@ -10,21 +10,33 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 // Offsets (bytes) of the two per-chunk arrays inside the MFMA path's workspace.
 struct WorkspacePlan {
-    size_t oT, oP, total;
+    size_t oT, oP, oS, total;
 };
+// L tokens per head of which the first L - L % chunk (whole flow blocks) go through the MFMA
+// kernels; when a tail remains, a state buffer carries S from them to the kernel of the tail.
 WorkspacePlan plan_workspace(int heads, int L, int d, int r, int chunk)
 {
-    (void)d;
     const size_t n = (size_t)chunk * r;
-    const size_t tok = (size_t)heads * L;          // tokens over all heads
-    const size_t tb = tok / chunk * n * n * 2;     // Tt: bf16, n*n per chunk
-    const size_t pb = tok * n * 2;                 // Pt: bf16, chunk*n per chunk
+    const size_t tok = (size_t)heads * (L - L % chunk);   // tokens in whole blocks over all heads
+    const size_t tb = tok / chunk * n * n * 2;            // Tt: bf16, n*n per block
+    const size_t pb = tok * n * 2;                        // Pt: bf16, chunk*n per block
+    const size_t sb = L % chunk ? (size_t)heads * d * d * 4 : 0;
     WorkspacePlan p;
     size_t o = 0;
     p.oT = o; o = round_up(o + tb, kAlign);
     p.oP = o; o = round_up(o + pb, kAlign);
+    p.oS = o; o = round_up(o + sb, kAlign);
     p.total = o;
     return p;
+}
+
+// Tokens per chunk for the generic kernel when it takes the ragged tail of an MFMA-path call:
+// the largest power of two up to 16 whose working set fits LDS next to the fp32 state (0: none).
+int tail_chunk(int d, int r)
+{
+    for (int c = 16; c >= 1; c /= 2)
+        if (pf::generic_lds_bytes(d, d, r, c) <= pf::kMaxLdsBytes) return c;
+    return 0;
 }
 
 // Tokens per flow block on the MFMA path: the requested chunk, halved until chunk * r virtual
@@ -68,7 +80,7 @@ const char *pf_status_str(pf_status s)
     switch (s) {
     case PF_OK: return "ok";
     case PF_ERR_NULL: return "a required pointer is NULL";
-    case PF_ERR_SHAPE: return "bad dimension (non-positive, or L not a multiple of chunk on the MFMA path)";
+    case PF_ERR_SHAPE: return "bad dimension (non-positive, or L not a multiple of chunk where that is required)";
     case PF_ERR_UNSUPPORTED: return "no kernel instance for these dimensions and dtype";
     case PF_ERR_ALIGN: return "a base address is not 16-byte aligned";
     case PF_ERR_WORKSPACE: return "workspace is NULL or too small";
@@ -91,8 +103,11 @@ int pf_delta_fwd_block(int d_k, int d_v, int r, int chunk, pf_dtype dt)
 size_t pf_delta_fwd_workspace_bytes(int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt)
 {
     if (check_dims(B, H, L, d_k, d_v, r, chunk) != PF_OK) return 0;
-    if (family(d_k, d_v, r, chunk, dt) != 2 || L % chunk != 0) return 0;
-    return plan_workspace(B * H, L, d_k, r, mfma_block(d_k, d_v, r, chunk, dt)).total;
+    if (family(d_k, d_v, r, chunk, dt) != 2) return 0;
+    const int block = mfma_block(d_k, d_v, r, chunk, dt);
+    if (L < block) return 0;                         // all of it is tail: generic kernel, no scratch
+    if (L % block != 0 && tail_chunk(d_k, r) == 0) return 0;
+    return plan_workspace(B * H, L, d_k, r, block).total;
 }
 
 pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
@@ -103,30 +118,43 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
     pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
     if (st != PF_OK) return st;
     int fam = family(d_k, d_v, r, chunk, dt);
-    // The MFMA path needs whole chunks; a ragged L goes to the generic path when that fits.
-    if (fam == 2 && L % chunk != 0)
-        fam = (pf::generic_lds_bytes(d_k, d_v, r, chunk) <= pf::kMaxLdsBytes) ? 1 : -1;
-    if (fam == -1) return PF_ERR_SHAPE;
     if (fam == 0) return PF_ERR_UNSUPPORTED;
+    // The MFMA kernels take whole flow blocks; the L % block tokens left over at the end of
+    // every head go through the generic kernel, from the state the blocks leave behind.
+    const int block = fam == 2 ? mfma_block(d_k, d_v, r, chunk, dt) : chunk;
+    const int tail = fam == 2 ? L % block : 0;
+    const int tchunk = tail ? tail_chunk(d_k, r) : 0;
+    if (tail && tchunk == 0) return PF_ERR_SHAPE;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(beta) || !aligned16(O) ||
         !aligned16(S0) || !aligned16(S_L))
         return PF_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int heads = B * H;
-    if (fam == 1 || L == 0) {
-        hipError_t e = pf::launch_generic(Q, K, V, beta, S0, O, S_L, heads, L, d_k, d_v, r, chunk,
-                                          dt == PF_BF16, s);
+    if (fam == 1 || L < block) {
+        // generic family, an empty sequence, or a sequence shorter than one flow block
+        hipError_t e = pf::launch_generic(Q, K, V, beta, S0, O, S_L, heads, L, d_k, d_v, r,
+                                          fam == 1 ? chunk : (tchunk ? tchunk : 1), dt == PF_BF16, s);
         return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
     }
-    const int block = mfma_block(d_k, d_v, r, chunk, dt);
     const WorkspacePlan wp = plan_workspace(heads, L, d_k, r, block);
     if (!workspace || workspace_bytes < wp.total) return PF_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PF_ERR_ALIGN;
     char *ws = static_cast<char *>(workspace);
-    hipError_t e = pf::launch_chunk_flow(Q, K, beta, ws + wp.oT, ws + wp.oP, heads, L, d_k, r, block, s);
-    if (e != hipSuccess) return PF_ERR_LAUNCH;
-    e = pf::launch_chunk_scan(Q, K, V, beta, ws + wp.oT, ws + wp.oP, S0, O, S_L, heads, L, d_k, r, block, s);
-    return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+    const float *state = S0;                       // state entering the tail
+    {
+        float *Smid = tail ? reinterpret_cast<float *>(ws + wp.oS) : S_L;
+        hipError_t e = pf::launch_chunk_flow(Q, K, beta, ws + wp.oT, ws + wp.oP, heads, L, d_k, r, block, s);
+        if (e != hipSuccess) return PF_ERR_LAUNCH;
+        e = pf::launch_chunk_scan(Q, K, V, beta, ws + wp.oT, ws + wp.oP, S0, O, Smid, heads, L, d_k, r, block, s);
+        if (e != hipSuccess) return PF_ERR_LAUNCH;
+        state = Smid;
+    }
+    if (tail) {
+        hipError_t e = pf::launch_generic(Q, K, V, beta, state, O, S_L, heads, L, d_k, d_v, r, tchunk, true, s,
+                                          L - tail);
+        if (e != hipSuccess) return PF_ERR_LAUNCH;
+    }
+    return PF_OK;
 }
 
 int pf_flow_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt)

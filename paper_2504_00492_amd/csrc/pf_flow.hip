@@ -62,7 +62,7 @@ struct FlowLds {
 template <int D, int N, int C>
 __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
     const bf16 *__restrict__ Q, const bf16 *__restrict__ K, const bf16 *__restrict__ beta,
-    bf16 *__restrict__ Tt, bf16 *__restrict__ Pt, int nchunks)
+    bf16 *__restrict__ Tt, bf16 *__restrict__ Pt, int nchunks, int NC, int tail)
 {
     using Ld = FlowLds<D, N, C>;
     constexpr int R = N / C;          // rank: virtual tokens per token
@@ -93,17 +93,20 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
     bf16 breg = (bf16)0.0f;   // kept as loaded: converting here would wait for the fetch
     static_assert(N <= NTHR, "beta of a chunk is fetched by one pass");
 
+    // A head holds NC whole blocks followed by `tail` tokens that another kernel takes: block c
+    // of the compact numbering starts (c / NC) * tail tokens further on in Q, K, beta.
+    auto skew = [&](size_t c) { return tail ? (c / (size_t)NC) * (size_t)tail : (size_t)0; };
     auto fetch_k = [&](size_t c) {
-        const bf16 *Kg = K + c * (size_t)N * D;
+        const bf16 *Kg = K + (c * (size_t)N + skew(c) * R) * D;
 #pragma unroll
         for (int q = 0; q < KV; ++q) {
             const int v = tid0 + NTHR * q;
             if ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8) kreg[q] = ld8(Kg + (size_t)v * 8);
         }
-        breg = beta[c * (size_t)N + (tid0 % N)];   // every thread loads: no branch, always in range
+        breg = beta[c * (size_t)N + skew(c) * R + (tid0 % N)];   // every thread loads: no branch, always in range
     };
     auto fetch_q = [&](size_t c) {
-        const bf16 *Qg = Q + c * (size_t)C * D;
+        const bf16 *Qg = Q + (c * (size_t)C + skew(c)) * D;
 #pragma unroll
         for (int q = 0; q < QV; ++q) {
             const int v = tid0 + NTHR * q;
@@ -366,7 +369,7 @@ bool mfma_instance_exists(int d, int n, int chunk)
 
 template <int D, int N, int C>
 static hipError_t launch_flow_instance(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,
-                                       size_t nchunks, hipStream_t stream)
+                                       size_t nchunks, int NC, int tail, hipStream_t stream)
 {
     auto kern = flow_kernel<D, N, C>;
     constexpr size_t lds = FlowLds<D, N, C>::total;
@@ -388,20 +391,21 @@ static hipError_t launch_flow_instance(const void *Q, const void *K, const void 
     const size_t resident = kNumCUs * (per_cu > 2 ? 2 : per_cu);
     const unsigned grid = (unsigned)(nchunks < resident ? nchunks : resident);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kFlowThreads), lds, stream, (const bf16 *)Q,
-                       (const bf16 *)K, (const bf16 *)beta, (bf16 *)Tt, (bf16 *)Pt, (int)nchunks);
+                       (const bf16 *)K, (const bf16 *)beta, (bf16 *)Tt, (bf16 *)Pt, (int)nchunks, NC, tail);
     return hipGetLastError();
 }
 
 hipError_t launch_chunk_flow(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,
                              int heads, int L, int d, int r, int chunk, hipStream_t stream)
 {
-    const size_t nchunks = (size_t)heads * (L / chunk);
+    const int NC = L / chunk, tail = L % chunk;   // the tail tokens of every head are skipped
+    const size_t nchunks = (size_t)heads * NC;
     if (nchunks == 0) return hipSuccess;
     if (nchunks > 0x7fffffffull) return hipErrorInvalidValue;
     const int n = chunk * r;
 #define X(DD, NN, CC)                                                                        \
     if (d == DD && n == NN && chunk == CC)                                                    \
-        return launch_flow_instance<DD, NN, CC>(Q, K, beta, Tt, Pt, nchunks, stream);
+        return launch_flow_instance<DD, NN, CC>(Q, K, beta, Tt, Pt, nchunks, NC, tail, stream);
     PF_FLOW_INSTANCES(X)
 #undef X
     return hipErrorInvalidValue;

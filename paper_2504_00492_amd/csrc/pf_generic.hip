@@ -62,7 +62,7 @@ template <typename T, bool kDrivers>
 __global__ __launch_bounds__(256) void generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                       const T *__restrict__ V, const T *__restrict__ beta,
                                                       const float *S0, T *__restrict__ O, float *SL,
-                                                      int L, int dk, int dv, int r, int chunk)
+                                                      int L, int dk, int dv, int r, int chunk, int t0)
 {
     extern __shared__ float smem[];
     const GenericPlan pl = generic_plan(dk, dv, r, chunk);
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256) void generic_kernel(const T *__restrict__ Q, c
     }
     __syncthreads();
 
-    for (int c0 = 0; c0 < L; c0 += chunk) {
+    for (int c0 = t0; c0 < L; c0 += chunk) {   // tokens before t0 belong to another kernel
         const int cl = min(chunk, L - c0);   // tokens in this chunk (shorter tail allowed)
         const int n = cl * r;                // virtual tokens in this chunk
         // ---- load: K, W = beta K, U = beta V, Q
@@ -179,7 +179,7 @@ size_t generic_lds_bytes(int dk, int dv, int r, int chunk)
 template <typename T, bool kDrivers>
 static hipError_t launch_generic_instance(const void *Q, const void *K, const void *V, const void *beta,
                                           const float *S0, void *O, float *SL, int heads, int L, int dk, int dv,
-                                          int r, int chunk, hipStream_t stream)
+                                          int r, int chunk, int t0, hipStream_t stream)
 {
     const size_t lds = generic_lds_bytes(dk, dv, r, chunk);
     auto kern = generic_kernel<T, kDrivers>;
@@ -187,24 +187,24 @@ static hipError_t launch_generic_instance(const void *Q, const void *K, const vo
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(heads), dim3(256), lds, stream, (const T *)Q, (const T *)K, (const T *)V,
-                       (const T *)beta, S0, (T *)O, SL, L, dk, dv, r, chunk);
+                       (const T *)beta, S0, (T *)O, SL, L, dk, dv, r, chunk, t0);
     return hipGetLastError();
 }
 
 hipError_t launch_generic(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
                           void *O, float *SL, int heads, int L, int dk, int dv, int r, int chunk,
-                          bool is_bf16, hipStream_t stream)
+                          bool is_bf16, hipStream_t stream, int t0)
 {
-    return is_bf16 ? launch_generic_instance<uint16_t, false>(Q, K, V, beta, S0, O, SL, heads, L, dk, dv, r, chunk, stream)
-                   : launch_generic_instance<float, false>(Q, K, V, beta, S0, O, SL, heads, L, dk, dv, r, chunk, stream);
+    return is_bf16 ? launch_generic_instance<uint16_t, false>(Q, K, V, beta, S0, O, SL, heads, L, dk, dv, r, chunk, t0, stream)
+                   : launch_generic_instance<float, false>(Q, K, V, beta, S0, O, SL, heads, L, dk, dv, r, chunk, t0, stream);
 }
 
 hipError_t launch_generic_drivers(const void *Q, const void *A, const void *Atil, const void *Bm, const float *S0,
                                   void *O, float *SL, int heads, int L, int dk, int dv, int r, int chunk,
                                   bool is_bf16, hipStream_t stream)
 {
-    return is_bf16 ? launch_generic_instance<uint16_t, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, stream)
-                   : launch_generic_instance<float, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, stream);
+    return is_bf16 ? launch_generic_instance<uint16_t, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, 0, stream)
+                   : launch_generic_instance<float, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, 0, stream);
 }
 
 }  // namespace pf

@@ -12,15 +12,17 @@ constexpr size_t kNumCUs = 256;              // compute units of one MI355X
 
 // ---- generic path (pf_generic.hip)
 size_t generic_lds_bytes(int dk, int dv, int r, int chunk);
+// tokens [t0, L) of every head; the heads are L tokens apart in memory
 hipError_t launch_generic(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
                           void *O, float *SL, int heads, int L, int dk, int dv, int r, int chunk,
-                          bool is_bf16, hipStream_t stream);
+                          bool is_bf16, hipStream_t stream, int t0 = 0);
 // general drivers (A, Atil, B) of Section 3.1 through the same kernel
 hipError_t launch_generic_drivers(const void *Q, const void *A, const void *Atil, const void *Bm,
                                   const float *S0, void *O, float *SL, int heads, int L, int dk, int dv,
                                   int r, int chunk, bool is_bf16, hipStream_t stream);
 
-// ---- MFMA path (pf_flow.hip, pf_scan.hip); d = d_k = d_v, n = chunk * r
+// ---- MFMA path (pf_flow.hip, pf_scan.hip); d = d_k = d_v, n = chunk * r.  Both launchers take
+// the first L / chunk whole blocks of every head (heads L tokens apart) and leave the tail alone.
 bool mfma_instance_exists(int d, int n, int chunk);
 hipError_t launch_chunk_flow(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,
                              int heads, int L, int d, int r, int chunk, hipStream_t stream);

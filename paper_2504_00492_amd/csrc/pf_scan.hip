@@ -80,7 +80,7 @@ template <int D, int N, int C, int TV>
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     const bf16 *__restrict__ Q, const bf16 *__restrict__ K, const bf16 *__restrict__ V,
     const bf16 *__restrict__ beta, const bf16 *__restrict__ Tt, const bf16 *__restrict__ Pt,
-    const float *S0, bf16 *__restrict__ O, float *SL, int nchains, int NC)
+    const float *S0, bf16 *__restrict__ O, float *SL, int nchains, int NC, int tail)
 {
     using Ld = ScanLds<D, N, C, TV>;
     constexpr int R = N / C;
@@ -121,6 +121,13 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     const size_t chain = blockIdx.x % nchains;
     const int dv0 = tile * TV;
     const size_t c0 = chain * (size_t)NC;
+    // A head holds NC whole blocks followed by `tail` tokens that another kernel takes: in Q, K,
+    // V, beta, O this head starts chain * tail tokens after its place in the compact numbering.
+    Q += chain * (size_t)tail * D;
+    K += chain * (size_t)tail * R * D;
+    V += chain * (size_t)tail * R * D;
+    beta += chain * (size_t)tail * R;
+    O += chain * (size_t)tail * D;
 
     // ------------------------------------------------------------------ state waves
     auto state_wave = [&](auto Wc) {
@@ -569,7 +576,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 template <int D, int N, int C, int TV>
 static hipError_t launch_scan_instance(const void *Q, const void *K, const void *V, const void *beta,
                                        const void *Tt, const void *Pt, const float *S0, void *O, float *SL,
-                                       int heads, int NC, hipStream_t stream)
+                                       int heads, int NC, int tail, hipStream_t stream)
 {
     auto kern = scan_kernel<D, N, C, TV>;
     constexpr size_t lds = ScanLds<D, N, C, TV>::total;
@@ -588,7 +595,7 @@ static hipError_t launch_scan_instance(const void *Q, const void *K, const void 
     const unsigned grid = (unsigned)heads * (D / TV);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kScanThreads), lds, stream, (const bf16 *)Q,
                        (const bf16 *)K, (const bf16 *)V, (const bf16 *)beta, (const bf16 *)Tt,
-                       (const bf16 *)Pt, S0, (bf16 *)O, SL, heads, NC);
+                       (const bf16 *)Pt, S0, (bf16 *)O, SL, heads, NC, tail);
     return hipGetLastError();
 }
 
@@ -596,7 +603,7 @@ hipError_t launch_chunk_scan(const void *Q, const void *K, const void *V, const 
                              const void *Pt, const float *S0, void *O, float *SL, int heads, int L, int d,
                              int r, int chunk, hipStream_t stream)
 {
-    const int NC = L / chunk;
+    const int NC = L / chunk, tail = L % chunk;   // the tail tokens of every head are skipped
     const int n = chunk * r;
     if ((long long)heads * (d / 16) > 0x7fffffffLL) return hipErrorInvalidValue;
     // d_v tile per workgroup: 32 rows when that already gives at least one workgroup per CU,
@@ -607,9 +614,9 @@ hipError_t launch_chunk_scan(const void *Q, const void *K, const void *V, const 
     if (d == DD && n == NN && chunk == CC) {                                                                \
         if constexpr (NN < 256) {                                                                           \
             if (wide)                                                                                       \
-                return launch_scan_instance<DD, NN, CC, 32>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, stream); \
+                return launch_scan_instance<DD, NN, CC, 32>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, stream); \
         }                                                                                                   \
-        return launch_scan_instance<DD, NN, CC, 16>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, stream);   \
+        return launch_scan_instance<DD, NN, CC, 16>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, stream);   \
     }
     PF_SCAN_INSTANCES(X)
 #undef X

@@ -78,7 +78,9 @@ def test_workspace_bytes(pf):
     b = pf.pf_delta_fwd_workspace_bytes(4, 16, 4096, 128, 128, 2, 64, BF)
     tok = 4 * 16 * 4096
     assert b >= tok // 64 * 128 * 128 * 2 + tok * 128 * 2 and b % 256 == 0
-    assert pf.pf_delta_fwd_workspace_bytes(4, 16, 4097, 128, 128, 2, 64, BF) == 0   # ragged -> generic or error
+    # a ragged tail adds the state hand-over buffer to the whole blocks' scratch
+    assert pf.pf_delta_fwd_workspace_bytes(4, 16, 4097, 128, 128, 2, 64, BF) == b + 4 * 16 * 128 * 128 * 4
+    assert pf.pf_delta_fwd_workspace_bytes(4, 16, 63, 128, 128, 2, 64, BF) == 0       # shorter than one block
     assert pf.pf_delta_fwd_workspace_bytes(0, 16, 4096, 128, 128, 2, 64, BF) == 0
 
 
@@ -102,7 +104,6 @@ def test_argument_checks_return_before_launch(pf):
     assert call(L=-1) == pf.PF_ERR_SHAPE
     assert call(r=0) == pf.PF_ERR_SHAPE
     assert call(chunk=0) == pf.PF_ERR_SHAPE
-    assert call(L=100) == pf.PF_ERR_SHAPE              # MFMA shape, ragged L, too big for the generic path
     assert call(dt=5) == pf.PF_ERR_UNSUPPORTED
     assert call(dt=pf.PF_F32) == pf.PF_ERR_UNSUPPORTED  # fp32 with d = 128, n = 128 does not fit LDS
     assert call(Q=A + 2) == pf.PF_ERR_ALIGN

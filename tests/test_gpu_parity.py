@@ -275,3 +275,36 @@ def test_chunk_beyond_one_flow_block(pf, oracle):
     O64, S64 = pf.delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], chunk=64)
     torch.cuda.synchronize()
     assert torch.equal(O128, O64) and torch.equal(S128, S64)
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("cfg2", dict(B=1, H=3, L=3 * 64 + 37)),          # whole blocks + a tail of 37 tokens
+    ("cfg3b", dict(B=1, H=2, L=2 * 64 + 5)),          # chunk 128 -> blocks of 64, tail 5, S0 != 0
+    ("cfg1", dict(B=2, H=2, L=64 + 63)),              # d = 64, tail one token short of a block
+    ("cfg4", dict(B=1, H=2, L=100)),                  # shorter than one block (128): all of it is tail
+])
+def test_mfma_path_ragged_length(pf, oracle, name, kw):
+    """L need not be a multiple of the flow block: the tail of every head runs on the generic
+    kernel from the state the whole blocks leave behind."""
+    import torch
+    w = synth.WORKLOADS[name].with_(**kw)
+    _check(pf, oracle, w, expect_family=None)
+    assert pf.pf_delta_fwd_supported(w.d_k, w.d_v, w.r, w.chunk, pf.PF_BF16) == 2
+    # S_L == NULL and in-place state with a tail
+    inp = synth.make_inputs(w)
+    dev = to_device(w, inp)
+    B, H, L, r, d = w.B, w.H, w.L, w.r, w.d_k
+    need = pf.pf_delta_fwd_workspace_bytes(B, H, L, d, d, r, w.chunk, pf.PF_BF16)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda:0")
+    O1, S1 = pf.delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], chunk=w.chunk, workspace=ws)
+    O2 = torch.empty_like(O1)
+    st = pf.pf_delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], O2, None, B, H, L, d, d, r, w.chunk,
+                         pf.PF_BF16, ws, need)
+    assert st == pf.PF_OK
+    S = dev["S0"].clone() if dev["S0"] is not None else torch.zeros(B, H, d, d, dtype=torch.float32, device="cuda:0")
+    O3 = torch.empty_like(O1)
+    st = pf.pf_delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], S, O3, S, B, H, L, d, d, r, w.chunk,
+                         pf.PF_BF16, ws, need)
+    assert st == pf.PF_OK
+    torch.cuda.synchronize()
+    assert torch.equal(O2, O1) and torch.equal(O3, O1) and torch.equal(S, S1)
