@@ -15,8 +15,9 @@
 //   state waves (0..3)  run the chain: R (interval 0), U_eff (interval 1), S update (interval 2).
 //                       Their global loads are their own T tiles, straight into MFMA operand
 //                       registers, one chunk ahead.  For n <= 128 they also compute O: S and
-//                       U_eff are already in their registers as operands of the chain, so
-//                       Q S^T and U_eff^T P^T cost them no LDS reads but Q.
+//                       U_eff are already in their registers as operands of the chain, and Q
+//                       of a wave's token tiles is loaded straight into operand registers,
+//                       so Q S^T and U_eff^T P^T cost no LDS reads.
 //   io waves (4..7)     do everything that can be late or early: staging of the next chunk's K,
 //                       V tile, Q, beta from registers into LDS and the loads of the chunk after
 //                       it (spread over the intervals), the coalesced copy of the previous O tile
@@ -167,6 +168,18 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             }
         };
 
+        // Q of this wave's token tiles, straight from global memory in B-operand form (16 rows x
+        // 64 bytes per load: only a few loads per step, so the poor coalescing does not matter)
+        bf16x8 bQ[T2][NKS];
+        auto fetch_q = [&](size_t cid) {
+            const bf16 *Qc = Q + cid * (size_t)C * D;
+#pragma unroll
+            for (int i = 0; i < T2; ++i)
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks)
+                    bQ[i][ks] = ld8(Qc + (size_t)(16 * tok_tile(i) + r16) * D + 32 * ks + 8 * g);
+        };
+
         bf16x8 t1[M1][NKT];        // T tiles of this wave's rows of U_eff (those below the diagonal)
         auto fetch_t = [&](size_t cid) {
             const bf16 *Tc = Tt + cid * (size_t)N * N;
@@ -180,7 +193,10 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         };
         if (NC > 0) {
             fetch_t(c0);
-            if constexpr (kStateReadout) fetch_p(c0);
+            if constexpr (kStateReadout) {
+                fetch_p(c0);
+                fetch_q(c0);
+            }
         }
         __syncthreads();
 
@@ -202,7 +218,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             // ---- interval 0: R = beta (.) (V - K S^T), rows (virtual tokens) dealt to the waves
             f32x4 oacc[T2][NNT];
             {
-                bf16x8 bS[NNT][NKS], aK[M1][NKS], bQ[T2][NKS];
+                bf16x8 bS[NNT][NKS], aK[M1][NKS];
                 bf16x4 vt[M1][NNT];
                 f32x4 bt[M1];
 #pragma unroll
@@ -221,13 +237,6 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 #pragma unroll
                     for (int nt = 0; nt < NNT; ++nt)
                         vt[i][nt] = lds_read_tr4(&Vs[(16 * mt + 4 * g + (r16 >> 2)) * VP + 16 * nt + 4 * (r16 & 3)]);
-                }
-                if constexpr (kStateReadout) {
-#pragma unroll
-                    for (int i = 0; i < T2; ++i)
-#pragma unroll
-                        for (int ks = 0; ks < NKS; ++ks)
-                            bQ[i][ks] = ld8(&Qs[(16 * tok_tile(i) + r16) * KP + 32 * ks + 8 * g]);
                 }
                 LDS_FENCE();
 #pragma unroll
@@ -258,6 +267,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 #pragma unroll
                             for (int md = 0; md < NNT; ++md) oacc[i][md] = mfma16(bS[md][ks], bQ[i][ks], oacc[i][md]);
                     }
+                    fetch_q(nx);
                 }
             }
             __syncthreads();
@@ -408,10 +418,12 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 v = v < N * PPR ? v : N * PPR - 1;                 // clamp instead of branching
                 vreg[q] = ld8(Vg + (size_t)(v / PPR) * D + (v % PPR) * 8);
             }
+            if constexpr (!kStateReadout) {
 #pragma unroll
-            for (int q = 0; q < QV; ++q) {
-                const int v = tb + NTHR * q;
-                if ((q + 1) * NTHR <= C * D / 8 || v < C * D / 8) qreg[q] = ld8(Qg + (size_t)v * 8);
+                for (int q = 0; q < QV; ++q) {
+                    const int v = tb + NTHR * q;
+                    if ((q + 1) * NTHR <= C * D / 8 || v < C * D / 8) qreg[q] = ld8(Qg + (size_t)v * 8);
+                }
             }
             breg = beta[cid * (size_t)N + (tb % N)];
         };
@@ -439,10 +451,12 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 const int v = tb + NTHR * q;
                 if (v < N * PPR) st8(&Vs[(v / PPR) * VP + (v % PPR) * 8], vreg[q]);
             }
+            if constexpr (!kStateReadout) {
 #pragma unroll
-            for (int q = 0; q < QV; ++q) {
-                const int v = tb + NTHR * q;
-                if ((q + 1) * NTHR <= C * D / 8 || v < C * D / 8) st8(&Qs[(v / VPR) * KP + (v % VPR) * 8], qreg[q]);
+                for (int q = 0; q < QV; ++q) {
+                    const int v = tb + NTHR * q;
+                    if ((q + 1) * NTHR <= C * D / 8 || v < C * D / 8) st8(&Qs[(v / VPR) * KP + (v % VPR) * 8], qreg[q]);
+                }
             }
             if (tb < N) bs[tb] = (float)breg;
         };
