@@ -19,7 +19,7 @@
 //                       of a wave's token tiles is loaded straight into operand registers,
 //                       so Q S^T and U_eff^T P^T cost no LDS reads.
 //   io waves (4..7)     do everything that can be late or early: staging of the next chunk's K,
-//                       V tile, Q, beta from registers into LDS and the loads of the chunk after
+//                       V tile, beta from registers into LDS and the loads of the chunk after
 //                       it (spread over the intervals), the coalesced copy of the previous O tile
 //                       to global memory, and for n = 256 (where the state waves have no
 //                       registers to spare) Q S^T (interval 0) and U_eff^T P^T (interval 2).
@@ -57,19 +57,18 @@ constexpr int kScanThreads = 2 * kScanRoleThreads;
 
 template <int D, int N, int C, int TV>
 struct ScanLds {
-    static constexpr int KP = D + 8;   // pitch of a row of K / Q
+    static constexpr int KP = D + 8;   // pitch of a row of K
     static constexpr int VP = TV + 8;  // pitch of a row (virtual token) of the V tile
     static constexpr int SP = D + 8;   // pitch of a row of the bf16 state copy
     static constexpr int UP = N + 8;   // pitch of a row of R^T / U_eff^T
     static constexpr int OP = TV + 8;  // pitch of a row (one token) of the staged O tile
     static constexpr size_t szK = (size_t)N * KP * 2;
-    static constexpr size_t rest = (size_t)N * VP * 2 + (size_t)C * KP * 2 + (size_t)N * 4 +
+    static constexpr size_t rest = (size_t)N * VP * 2 + (size_t)N * 4 +
                                    (size_t)TV * SP * 2 + (size_t)2 * TV * UP * 2 + (size_t)C * OP * 2;
     static constexpr bool kDoubleK = 2 * szK + rest <= (size_t)kMaxLdsBytes;
     static constexpr size_t oKs = 0;
     static constexpr size_t oVs = oKs + (kDoubleK ? 2 : 1) * szK;
-    static constexpr size_t oQs = oVs + (size_t)N * VP * 2;
-    static constexpr size_t oBs = oQs + (size_t)C * KP * 2;
+    static constexpr size_t oBs = oVs + (size_t)N * VP * 2;
     static constexpr size_t oSb = oBs + (size_t)N * 4;
     static constexpr size_t oRs = oSb + (size_t)TV * SP * 2;
     static constexpr size_t oUe = oRs + (size_t)TV * UP * 2;
@@ -106,7 +105,6 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16 *Ks = reinterpret_cast<bf16 *>(smem + Ld::oKs);
     bf16 *Vs = reinterpret_cast<bf16 *>(smem + Ld::oVs);
-    bf16 *Qs = reinterpret_cast<bf16 *>(smem + Ld::oQs);
     float *bs = reinterpret_cast<float *>(smem + Ld::oBs);
     bf16 *Sb = reinterpret_cast<bf16 *>(smem + Ld::oSb);
     bf16 *Rs = reinterpret_cast<bf16 *>(smem + Ld::oRs);
@@ -385,11 +383,10 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 
         constexpr int VPR = D / 8;                                 // 16-byte vectors per row of K / Q
         constexpr int KV = (N * D / 8 + NTHR - 1) / NTHR;          // vectors of K per thread
-        constexpr int QV = (C * D / 8 + NTHR - 1) / NTHR;          // vectors of Q per thread
         constexpr int PPR = TV / 8;                                // 16-byte pieces per row of the V tile
         constexpr int VV = (N * PPR + NTHR - 1) / NTHR;            // vectors of the V tile per thread
         constexpr int OV = (C * PPR + NTHR - 1) / NTHR;            // vectors of the O tile per thread
-        bf16x8 kreg[KV], qreg[QV], vreg[VV];
+        bf16x8 kreg[KV], vreg[VV];
         bf16 breg = (bf16)0.0f;
         bf16x8 p2[T2][NKT];        // P tiles of this wave's token tiles (those the causal mask keeps)
 
@@ -411,19 +408,11 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         };
         auto fetch_vqb = [&](size_t cid) {
             const bf16 *Vg = V + cid * (size_t)N * D + dv0;
-            const bf16 *Qg = Q + cid * (size_t)C * D;
 #pragma unroll
             for (int q = 0; q < VV; ++q) {
                 int v = tb + NTHR * q;
                 v = v < N * PPR ? v : N * PPR - 1;                 // clamp instead of branching
                 vreg[q] = ld8(Vg + (size_t)(v / PPR) * D + (v % PPR) * 8);
-            }
-            if constexpr (!kStateReadout) {
-#pragma unroll
-                for (int q = 0; q < QV; ++q) {
-                    const int v = tb + NTHR * q;
-                    if ((q + 1) * NTHR <= C * D / 8 || v < C * D / 8) qreg[q] = ld8(Qg + (size_t)v * 8);
-                }
             }
             breg = beta[cid * (size_t)N + (tb % N)];
         };
@@ -436,6 +425,16 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 for (int kt = 0; kt < NKT; ++kt)
                     if (kt < ksteps_of(tt)) p2[i][kt] = ld8(Pc + ((size_t)(tt * NKT + kt) * 64 + lane) * 8);
             }
+        };
+        // Q of this wave's token tiles, straight from global memory in B-operand form
+        bf16x8 bQ[T2][NKS];
+        auto fetch_q = [&](size_t cid) {
+            const bf16 *Qc = Q + cid * (size_t)C * D;
+#pragma unroll
+            for (int i = 0; i < T2; ++i)
+#pragma unroll
+                for (int ks = 0; ks < NKS; ++ks)
+                    bQ[i][ks] = ld8(Qc + (size_t)(16 * tok_tile(i) + r16) * D + 32 * ks + 8 * g);
         };
         auto stage_k = [&](bf16 *Kd, int q0, int q1) {
 #pragma unroll
@@ -450,13 +449,6 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             for (int q = 0; q < VV; ++q) {
                 const int v = tb + NTHR * q;
                 if (v < N * PPR) st8(&Vs[(v / PPR) * VP + (v % PPR) * 8], vreg[q]);
-            }
-            if constexpr (!kStateReadout) {
-#pragma unroll
-                for (int q = 0; q < QV; ++q) {
-                    const int v = tb + NTHR * q;
-                    if ((q + 1) * NTHR <= C * D / 8 || v < C * D / 8) st8(&Qs[(v / VPR) * KP + (v % VPR) * 8], qreg[q]);
-                }
             }
             if (tb < N) bs[tb] = (float)breg;
         };
@@ -474,7 +466,10 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         if (NC > 0) {
             fetch_k(c0, 0, KV);
             fetch_vqb(c0);
-            if constexpr (!kStateReadout) fetch_p(c0);
+            if constexpr (!kStateReadout) {
+                fetch_p(c0);
+                fetch_q(c0);
+            }
             stage_k(Ks, 0, KV);
             stage_vqb();
             const size_t c1 = NC > 1 ? c0 + 1 : c0;
@@ -496,15 +491,11 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             if (ch > 0) copy_out(cid - 1);
             f32x4 oacc[T2][NNT];
             if constexpr (!kStateReadout) {
-                bf16x8 aS[NNT][NKS], bQ[T2][NKS];
+                bf16x8 aS[NNT][NKS];
 #pragma unroll
                 for (int md = 0; md < NNT; ++md)
 #pragma unroll
                     for (int ks = 0; ks < NKS; ++ks) aS[md][ks] = ld8(&Sb[(16 * md + r16) * SP + 32 * ks + 8 * g]);
-#pragma unroll
-                for (int i = 0; i < T2; ++i)
-#pragma unroll
-                    for (int ks = 0; ks < NKS; ++ks) bQ[i][ks] = ld8(&Qs[(16 * tok_tile(i) + r16) * KP + 32 * ks + 8 * g]);
                 LDS_FENCE();
 #pragma unroll
                 for (int i = 0; i < T2; ++i) {
@@ -515,6 +506,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 #pragma unroll
                         for (int md = 0; md < NNT; ++md) oacc[i][md] = mfma16(aS[md][ks], bQ[i][ks], oacc[i][md]);
                 }
+                fetch_q(n1);
             }
             bf16 *Knext = Ks + (kDoubleK ? ((ch + 1) & 1) * N * KP : 0);
             if (kDoubleK) {
@@ -523,8 +515,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             }
             __syncthreads();
 
-            // ---- interval 1: next chunk's V tile, Q, beta registers -> LDS, the chunk after it
-            // on its way
+            // ---- interval 1: next chunk's V tile and beta registers -> LDS, the chunk after it on
+            // its way
             stage_vqb();
             fetch_vqb(n2);
             __syncthreads();
