@@ -217,6 +217,10 @@ def main():
         "min_hbm_gbs": min_bytes / (ms_per_step * 1e-3) / 1e9,
         "frac_hbm_peak_min_traffic": min_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "kernels": kernels, "roofline": roofline,
+        # inputs + outputs + workspace of one step; below the 256 MB last-level cache the timed
+        # steps (same buffers every step) run cache-resident, not from HBM
+        "working_set_bytes": int(min_bytes + need + B * H * dv * dk * 4),
+        "cache_resident": bool(min_bytes + need + B * H * dv * dk * 4 < 256 * 2 ** 20),
     }
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload, plus parity on it
