@@ -33,6 +33,8 @@
 #include "pf_common.cuh"
 #include "pf_layout.h"
 
+#include <atomic>
+
 namespace pf {
 
 constexpr int kFlowThreads = 512;
@@ -375,7 +377,7 @@ static hipError_t launch_flow_instance(const void *Q, const void *K, const void 
     constexpr size_t lds = FlowLds<D, N, C>::total;
     static_assert(lds <= kMaxLdsBytes, "flow kernel LDS plan exceeds the CU");
     // the LDS opt-in is per device and sticks: ask once per device, not once per launch
-    static int armed_device = -1;
+    static std::atomic<int> armed_device{-1};
     int dev = -1;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;

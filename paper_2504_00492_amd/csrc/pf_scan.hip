@@ -45,6 +45,8 @@
 #include "pf_common.cuh"
 #include "pf_layout.h"
 
+#include <atomic>
+
 #include <type_traits>
 
 namespace pf {
@@ -588,7 +590,7 @@ static hipError_t launch_scan_instance(const void *Q, const void *K, const void 
     constexpr size_t lds = ScanLds<D, N, C, TV>::total;
     static_assert(lds <= kMaxLdsBytes, "scan kernel LDS plan exceeds the CU");
     // the LDS opt-in is per device and sticks: ask once per device, not once per launch
-    static int armed_device = -1;
+    static std::atomic<int> armed_device{-1};
     int dev = -1;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;

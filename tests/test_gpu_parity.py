@@ -308,3 +308,36 @@ def test_mfma_path_ragged_length(pf, oracle, name, kw):
     assert st == pf.PF_OK
     torch.cuda.synchronize()
     assert torch.equal(O2, O1) and torch.equal(O3, O1) and torch.equal(S, S1)
+
+
+def test_calls_can_be_captured_in_a_graph(pf):
+    """pf_delta_fwd only enqueues kernels on the given stream (no allocation, no memset, no
+    synchronisation), so it can be recorded into a HIP graph; every replay, with eager work and
+    synchronisations in between, must reproduce the eager result bit for bit."""
+    import torch
+    w = synth.WORKLOADS["cfg2"].with_(B=1, H=4, L=256, s0_std=0.1)
+    inp = synth.make_inputs(w)
+    dev = to_device(w, inp)
+    B, H, L, r, d = w.B, w.H, w.L, w.r, w.d_k
+    need = pf.pf_delta_fwd_workspace_bytes(B, H, L, d, d, r, w.chunk, pf.PF_BF16)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    O_e, S_e = pf.delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], chunk=w.chunk, workspace=ws)
+    torch.cuda.synchronize()
+    O_g = torch.empty_like(O_e)
+    S_g = torch.empty_like(S_e)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        st = pf.pf_delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], O_g, S_g, B, H, L, d, d, r,
+                             w.chunk, pf.PF_BF16, ws, need, torch.cuda.current_stream())
+        assert st == pf.PF_OK
+    for rep in range(3):
+        O_g.fill_(float("nan"))
+        S_g.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O_g, O_e) and torch.equal(S_g, S_e), f"replay {rep}"
+        # eager work between replays (also on the same workspace)
+        O2, S2 = pf.delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], chunk=w.chunk, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(O2, O_e)
