@@ -10,8 +10,25 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 // Offsets (bytes) of the two per-chunk arrays inside the MFMA path's workspace.
 struct WorkspacePlan {
-    size_t oT, oP, oS, total;
+    size_t oT, oP, oS, oZ, oI, oH, oG, oSin, total;
+    int segments;
 };
+
+// Segments per head for the segment-parallel scan: 1 (plain hand-over chain per head) unless
+// the chains of the plain scan (heads x d_v tiles) would leave three quarters of the CUs idle
+// and there are enough blocks to cut.  Three passes of the scan kernel then run with
+// `segments` times as many chains; measured, eight segments pay (1.6-1.7x on 4 heads of 65536
+// tokens) and four only break even.
+int scan_segments(int heads, int L, int d, int r, int chunk)
+{
+    if (L % chunk != 0) return 1;
+    const int NC = L / chunk;
+    const long long chains = (long long)heads * (d / pf::scan_dv_tile(heads, d, chunk * r));
+    if (chains > 32 || NC < 32) return 1;
+    int G = 1;
+    while (2 * G * chains <= 256 && NC % (2 * G) == 0 && NC / (2 * G) >= 4) G *= 2;
+    return G >= 8 ? G : 1;
+}
 // L tokens per head of which the first L - L % chunk (whole flow blocks) go through the MFMA
 // kernels; when a tail remains, a state buffer carries S from them to the kernel of the tail.
 WorkspacePlan plan_workspace(int heads, int L, int d, int r, int chunk)
@@ -22,10 +39,17 @@ WorkspacePlan plan_workspace(int heads, int L, int d, int r, int chunk)
     const size_t pb = tok * n * 2;                        // Pt: bf16, chunk*n per block
     const size_t sb = L % chunk ? (size_t)heads * d * d * 4 : 0;
     WorkspacePlan p;
+    p.segments = scan_segments(heads, L, d, r, chunk);
+    const size_t gb = p.segments > 1 ? (size_t)heads * p.segments * d * d * 4 : 0;   // per-segment d x d fp32
     size_t o = 0;
     p.oT = o; o = round_up(o + tb, kAlign);
     p.oP = o; o = round_up(o + pb, kAlign);
     p.oS = o; o = round_up(o + sb, kAlign);
+    p.oZ = o; o = round_up(o + (gb ? n * d * 2 : 0), kAlign);
+    p.oI = o; o = round_up(o + (gb ? (size_t)d * d * 4 : 0), kAlign);
+    p.oH = o; o = round_up(o + gb, kAlign);
+    p.oG = o; o = round_up(o + gb, kAlign);
+    p.oSin = o; o = round_up(o + gb, kAlign);
     p.total = o;
     return p;
 }
@@ -143,8 +167,28 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
     const float *state = S0;                       // state entering the tail
     {
         float *Smid = tail ? reinterpret_cast<float *>(ws + wp.oS) : S_L;
+        const void *Tt = ws + wp.oT, *Pt = ws + wp.oP;
         hipError_t e = pf::launch_chunk_flow(Q, K, beta, ws + wp.oT, ws + wp.oP, heads, L, d_k, r, block, s);
         if (e != hipSuccess) return PF_ERR_LAUNCH;
+        if (wp.segments > 1) {
+            // Segment-parallel scan (no tail here): every segment of every head is a chain of
+            // its own.  What a segment does to a zero state, then its propagator (identity in,
+            // zero values), then the composition over the segments of a head, then the real
+            // pass of every segment from its true incoming state.
+            const int G = wp.segments, vh = heads * G, Ls = L / G;
+            float *Hseg = reinterpret_cast<float *>(ws + wp.oH), *Pseg = reinterpret_cast<float *>(ws + wp.oG);
+            float *Sin = reinterpret_cast<float *>(ws + wp.oSin), *ident = reinterpret_cast<float *>(ws + wp.oI);
+            e = pf::launch_segment_constants(ws + wp.oZ, ident, block * r, d_k, s);
+            if (e != hipSuccess) return PF_ERR_LAUNCH;
+            e = pf::launch_chunk_scan(Q, K, V, beta, Tt, Pt, nullptr, nullptr, Hseg, vh, Ls, d_k, r, block, s);
+            if (e != hipSuccess) return PF_ERR_LAUNCH;
+            e = pf::launch_chunk_scan(Q, K, ws + wp.oZ, beta, Tt, Pt, ident, nullptr, Pseg, vh, Ls, d_k, r, block, s, 0, 0);
+            if (e != hipSuccess) return PF_ERR_LAUNCH;
+            e = pf::launch_segment_compose(S0, Pseg, Hseg, Sin, S_L, heads, G, d_k, s);
+            if (e != hipSuccess) return PF_ERR_LAUNCH;
+            e = pf::launch_chunk_scan(Q, K, V, beta, Tt, Pt, Sin, O, nullptr, vh, Ls, d_k, r, block, s);
+            return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+        }
         e = pf::launch_chunk_scan(Q, K, V, beta, ws + wp.oT, ws + wp.oP, S0, O, Smid, heads, L, d_k, r, block, s);
         if (e != hipSuccess) return PF_ERR_LAUNCH;
         state = Smid;

@@ -28,6 +28,17 @@ hipError_t launch_chunk_flow(const void *Q, const void *K, const void *beta, voi
                              int heads, int L, int d, int r, int chunk, hipStream_t stream);
 hipError_t launch_chunk_scan(const void *Q, const void *K, const void *V, const void *beta,
                              const void *Tt, const void *Pt, const float *S0, void *O, float *SL,
-                             int heads, int L, int d, int r, int chunk, hipStream_t stream);
+                             int heads, int L, int d, int r, int chunk, hipStream_t stream,
+                             int vmul = 1, int s0mul = 1);
+// (O may be NULL: the state is advanced and S_L written, nothing is read out.)
+// d_v rows of S one scan workgroup owns for these dimensions (the scan runs heads * d / tile chains)
+int scan_dv_tile(int heads, int d, int n);
+
+// ---- segment-parallel scan (pf_segments.hip): S0 / V constants and the composition of segments
+// writes an n x d block of bf16 zeros at zeroV and the d x d fp32 identity at ident
+hipError_t launch_segment_constants(void *zeroV, float *ident, int n, int d, hipStream_t stream);
+// per head: Sin[0] = S0 (or 0); Sin[s+1] = Sin[s] Pseg[s] + Hseg[s]; S_L = Sin[G] (if not NULL)
+hipError_t launch_segment_compose(const float *S0, const float *Pseg, const float *Hseg, float *Sin,
+                                  float *SL, int heads, int G, int d, hipStream_t stream);
 
 }  // namespace pf

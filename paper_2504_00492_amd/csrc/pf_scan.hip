@@ -82,7 +82,7 @@ template <int D, int N, int C, int TV>
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     const bf16 *__restrict__ Q, const bf16 *__restrict__ K, const bf16 *__restrict__ V,
     const bf16 *__restrict__ beta, const bf16 *__restrict__ Tt, const bf16 *__restrict__ Pt,
-    const float *S0, bf16 *__restrict__ O, float *SL, int nchains, int NC, int tail)
+    const float *S0, bf16 *__restrict__ O, float *SL, int nchains, int NC, int tail, int vmul, int s0mul)
 {
     using Ld = ScanLds<D, N, C, TV>;
     constexpr int R = N / C;
@@ -124,11 +124,14 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     const size_t c0 = chain * (size_t)NC;
     // A head holds NC whole blocks followed by `tail` tokens that another kernel takes: in Q, K,
     // V, beta, O this head starts chain * tail tokens after its place in the compact numbering.
+    // vmul = 0 makes every block of every chain read the same n x d block at V (a block of
+    // zeros turns the kernel into the propagator of the transitions alone); s0mul = 0 makes
+    // every chain start from the same d x d matrix at S0 (the identity, for that propagator).
     Q += chain * (size_t)tail * D;
     K += chain * (size_t)tail * R * D;
-    V += chain * (size_t)tail * R * D;
+    V += (size_t)vmul * chain * (size_t)tail * R * D;
     beta += chain * (size_t)tail * R;
-    O += chain * (size_t)tail * D;
+    if (O) O += chain * (size_t)tail * D;
 
     // ------------------------------------------------------------------ state waves
     auto state_wave = [&](auto Wc) {
@@ -146,7 +149,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             for (int nt = 0; nt < NNT; ++nt) {
                 const int mt = W * MPW + a;
                 f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                if (S0) v = *reinterpret_cast<const f32x4 *>(S0 + chain * (size_t)D * D +
+                if (S0) v = *reinterpret_cast<const f32x4 *>(S0 + (size_t)s0mul * chain * (size_t)D * D +
                                                              (size_t)(dv0 + 16 * nt + r16) * D + 16 * mt + 4 * g);
                 sacc[a][nt] = v;
                 st4(&Sb[(16 * nt + r16) * SP + 16 * mt + 4 * g], cvt4(v));
@@ -409,7 +412,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             }
         };
         auto fetch_vqb = [&](size_t cid) {
-            const bf16 *Vg = V + cid * (size_t)N * D + dv0;
+            const bf16 *Vg = V + (size_t)vmul * cid * (size_t)N * D + dv0;
 #pragma unroll
             for (int q = 0; q < VV; ++q) {
                 int v = tb + NTHR * q;
@@ -456,6 +459,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         };
         // the O tile of one chunk (chunk tokens x TV features), LDS -> its rows of O
         auto copy_out = [&](size_t cid) {
+            if (!O) return;                                    // state-only pass: no readout wanted
             bf16 *Oc = O + cid * (size_t)C * D;
 #pragma unroll
             for (int q = 0; q < OV; ++q) {
@@ -584,7 +588,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 template <int D, int N, int C, int TV>
 static hipError_t launch_scan_instance(const void *Q, const void *K, const void *V, const void *beta,
                                        const void *Tt, const void *Pt, const float *S0, void *O, float *SL,
-                                       int heads, int NC, int tail, hipStream_t stream)
+                                       int heads, int NC, int tail, int vmul, int s0mul, hipStream_t stream)
 {
     auto kern = scan_kernel<D, N, C, TV>;
     constexpr size_t lds = ScanLds<D, N, C, TV>::total;
@@ -603,28 +607,33 @@ static hipError_t launch_scan_instance(const void *Q, const void *K, const void 
     const unsigned grid = (unsigned)heads * (D / TV);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kScanThreads), lds, stream, (const bf16 *)Q,
                        (const bf16 *)K, (const bf16 *)V, (const bf16 *)beta, (const bf16 *)Tt,
-                       (const bf16 *)Pt, S0, (bf16 *)O, SL, heads, NC, tail);
+                       (const bf16 *)Pt, S0, (bf16 *)O, SL, heads, NC, tail, vmul, s0mul);
     return hipGetLastError();
+}
+
+int scan_dv_tile(int heads, int d, int n)
+{
+    // 32 rows when that already gives at least one workgroup per CU, else 16 rows (twice the
+    // workgroups, half the MFMA work per operand byte).  With n = 256 only the 16-row tile
+    // fits LDS next to the chunk's K.
+    return (n < 256 && (long long)heads * (d / 32) >= 256) ? 32 : 16;
 }
 
 hipError_t launch_chunk_scan(const void *Q, const void *K, const void *V, const void *beta, const void *Tt,
                              const void *Pt, const float *S0, void *O, float *SL, int heads, int L, int d,
-                             int r, int chunk, hipStream_t stream)
+                             int r, int chunk, hipStream_t stream, int vmul, int s0mul)
 {
     const int NC = L / chunk, tail = L % chunk;   // the tail tokens of every head are skipped
     const int n = chunk * r;
     if ((long long)heads * (d / 16) > 0x7fffffffLL) return hipErrorInvalidValue;
-    // d_v tile per workgroup: 32 rows when that already gives at least one workgroup per CU,
-    // else 16 rows (twice the workgroups, half the MFMA work per operand byte).  With n = 256
-    // only the 16-row tile fits LDS next to the chunk's K.
-    const bool wide = (long long)heads * (d / 32) >= 256;
+    const bool wide = scan_dv_tile(heads, d, n) == 32;
 #define X(DD, NN, CC)                                                                                      \
     if (d == DD && n == NN && chunk == CC) {                                                                \
         if constexpr (NN < 256) {                                                                           \
             if (wide)                                                                                       \
-                return launch_scan_instance<DD, NN, CC, 32>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, stream); \
+                return launch_scan_instance<DD, NN, CC, 32>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, stream); \
         }                                                                                                   \
-        return launch_scan_instance<DD, NN, CC, 16>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, stream);   \
+        return launch_scan_instance<DD, NN, CC, 16>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, stream);   \
     }
     PF_SCAN_INSTANCES(X)
 #undef X

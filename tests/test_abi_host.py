@@ -84,6 +84,19 @@ def test_workspace_bytes(pf):
     assert pf.pf_delta_fwd_workspace_bytes(0, 16, 4096, 128, 128, 2, 64, BF) == 0
 
 
+def test_workspace_of_the_segment_parallel_scan(pf):
+    """Few heads, long sequence: 3 d x d fp32 matrices per segment plus the two constants."""
+    BF = pf.PF_BF16
+    d, r, C, L = 128, 2, 64, 65536
+    n = C * r
+    plain = lambda heads: heads * (L // C) * (n * n + C * n) * 2
+    b4 = pf.pf_delta_fwd_workspace_bytes(1, 4, L, d, d, r, C, BF)         # 32 chains -> 8 segments
+    assert b4 == plain(4) + n * d * 2 + d * d * 4 + 3 * 4 * 8 * d * d * 4
+    b8 = pf.pf_delta_fwd_workspace_bytes(1, 8, L, d, d, r, C, BF)         # 64 chains: plain scan
+    assert b8 == plain(8)
+    assert pf.pf_delta_fwd_workspace_bytes(1, 4, 1024, d, d, r, C, BF) == plain(4) * 1024 // L   # too short to cut
+
+
 def test_argument_checks_return_before_launch(pf):
     """Fake (never dereferenced) addresses: each call must fail its check on the host."""
     A = 0x10000  # 16-byte aligned fake device address

@@ -341,3 +341,34 @@ def test_calls_can_be_captured_in_a_graph(pf):
         O2, S2 = pf.delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], chunk=w.chunk, workspace=ws)
         torch.cuda.synchronize()
         assert torch.equal(O2, O_e)
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("cfg2", dict(B=1, H=2, L=4096)),                 # 16 chains -> 16 segments per head
+    ("cfg1", dict(B=1, H=1, L=2048, s0_std=0.2)),     # d = 64, one head, nonzero S0
+    ("cfg4", dict(B=1, H=3, L=4096, s0_std=0.1)),     # n = 256 instance, near-reflection betas
+])
+def test_segment_parallel_scan(pf, oracle, name, kw):
+    """Few heads and a long sequence: the library cuts every head into segments that run as
+    chains of their own (affine maps of the state compose, Proposition 2.1).  Same results as
+    the oracle, and the state may still be updated in place."""
+    import torch
+    w = synth.WORKLOADS[name].with_(**kw)
+    B, H, L, r, d = w.B, w.H, w.L, w.r, w.d_k
+    # the segment buffers show in the workspace size: more than T and P alone
+    n = w.chunk * r
+    plain = B * H * (L // w.chunk) * (n * n + w.chunk * n) * 2
+    need = pf.pf_delta_fwd_workspace_bytes(B, H, L, d, d, r, w.chunk, pf.PF_BF16)
+    assert need > plain + 3 * B * H * 4 * d * d * 4
+    _check(pf, oracle, w, expect_family=2)
+    inp = synth.make_inputs(w)
+    dev = to_device(w, inp)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    O1, S1 = pf.delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], chunk=w.chunk, workspace=ws)
+    S = dev["S0"].clone() if dev["S0"] is not None else torch.zeros(B, H, d, d, dtype=torch.float32, device="cuda:0")
+    O2 = torch.empty_like(O1)
+    st = pf.pf_delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], S, O2, S, B, H, L, d, d, r, w.chunk,
+                         pf.PF_BF16, ws, need)
+    assert st == pf.PF_OK
+    torch.cuda.synchronize()
+    assert torch.equal(O2, O1) and torch.equal(S, S1)
