@@ -78,7 +78,9 @@ struct ScanLds {
     static constexpr size_t total = oOb + (size_t)C * OP * 2;
 };
 
-template <int D, int N, int C, int TV>
+// RO: the readout O is wanted (false: only the state is advanced, for the per-segment passes of
+// the segment-parallel scan).
+template <int D, int N, int C, int TV, bool RO>
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     const bf16 *__restrict__ Q, const bf16 *__restrict__ K, const bf16 *__restrict__ V,
     const bf16 *__restrict__ beta, const bf16 *__restrict__ Tt, const bf16 *__restrict__ Pt,
@@ -99,7 +101,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     constexpr bool kDoubleK = Ld::kDoubleK;
     // Who computes O: the state waves when their register budget allows (they already hold S and
     // U_eff as operands, so it costs them no LDS reads but Q), else the io waves.
-    constexpr bool kStateReadout = N <= 128;
+    constexpr bool kStateReadout = RO && N <= 128;
+    constexpr bool kIoReadout = RO && N > 128;
     static_assert(D % 64 == 0 && TV % 16 == 0 && N % 32 == 0, "tile shapes");
     static_assert(MT % 4 == 0 && CT % 4 == 0, "every wave of a role owns the same number of tiles");
     static_assert(N <= NTHR, "beta of a chunk is fetched by one pass");
@@ -459,7 +462,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         };
         // the O tile of one chunk (chunk tokens x TV features), LDS -> its rows of O
         auto copy_out = [&](size_t cid) {
-            if (!O) return;                                    // state-only pass: no readout wanted
+            if constexpr (!RO) return;
             bf16 *Oc = O + cid * (size_t)C * D;
 #pragma unroll
             for (int q = 0; q < OV; ++q) {
@@ -472,7 +475,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         if (NC > 0) {
             fetch_k(c0, 0, KV);
             fetch_vqb(c0);
-            if constexpr (!kStateReadout) {
+            if constexpr (kIoReadout) {
                 fetch_p(c0);
                 fetch_q(c0);
             }
@@ -496,7 +499,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             // half of the next chunk's K into the buffer this step does not read
             if (ch > 0) copy_out(cid - 1);
             f32x4 oacc[T2][NNT];
-            if constexpr (!kStateReadout) {
+            if constexpr (kIoReadout) {
                 bf16x8 aS[NNT][NKS];
 #pragma unroll
                 for (int md = 0; md < NNT; ++md)
@@ -528,7 +531,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             __syncthreads();
 
             // ---- interval 2: O^T += U_eff^T P^T, O tile to LDS
-            if constexpr (!kStateReadout) {
+            if constexpr (kIoReadout) {
                 constexpr int KMAX = ksteps_of(tok_tile(T2 - 1)) > ksteps_of(tok_tile(0)) ? ksteps_of(tok_tile(T2 - 1))
                                                                                           : ksteps_of(tok_tile(0));
                 constexpr int KM = KMAX < NKT ? KMAX : NKT;
@@ -553,7 +556,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                         st4(&Ob[(16 * tt + r16) * OP + 16 * md + 4 * g], cvt4(oacc[i][md]));
                 }
             }
-            if constexpr (!kStateReadout) fetch_p(n1);
+            if constexpr (kIoReadout) fetch_p(n1);
             if (kDoubleK) {
                 stage_k(Knext, KH, KV);
                 fetch_k(n2, KH, KV);
@@ -585,12 +588,12 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     X(64, 64, 64) X(64, 128, 64) X(64, 128, 128) X(64, 256, 64) X(64, 256, 128) \
     X(128, 64, 64) X(128, 128, 64) X(128, 128, 128) X(128, 256, 64) X(128, 256, 128)
 
-template <int D, int N, int C, int TV>
-static hipError_t launch_scan_instance(const void *Q, const void *K, const void *V, const void *beta,
+template <int D, int N, int C, int TV, bool RO>
+static hipError_t launch_scan_ro(const void *Q, const void *K, const void *V, const void *beta,
                                        const void *Tt, const void *Pt, const float *S0, void *O, float *SL,
                                        int heads, int NC, int tail, int vmul, int s0mul, hipStream_t stream)
 {
-    auto kern = scan_kernel<D, N, C, TV>;
+    auto kern = scan_kernel<D, N, C, TV, RO>;
     constexpr size_t lds = ScanLds<D, N, C, TV>::total;
     static_assert(lds <= kMaxLdsBytes, "scan kernel LDS plan exceeds the CU");
     // the LDS opt-in is per device and sticks: ask once per device, not once per launch
@@ -617,6 +620,15 @@ int scan_dv_tile(int heads, int d, int n)
     // workgroups, half the MFMA work per operand byte).  With n = 256 only the 16-row tile
     // fits LDS next to the chunk's K.
     return (n < 256 && (long long)heads * (d / 32) >= 256) ? 32 : 16;
+}
+
+template <int D, int N, int C, int TV>
+static hipError_t launch_scan_instance(const void *Q, const void *K, const void *V, const void *beta,
+                                       const void *Tt, const void *Pt, const float *S0, void *O, float *SL,
+                                       int heads, int NC, int tail, int vmul, int s0mul, hipStream_t stream)
+{
+    return O ? launch_scan_ro<D, N, C, TV, true>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, stream)
+             : launch_scan_ro<D, N, C, TV, false>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, stream);
 }
 
 hipError_t launch_chunk_scan(const void *Q, const void *K, const void *V, const void *beta, const void *Tt,
