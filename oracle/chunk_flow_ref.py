@@ -113,23 +113,33 @@ def chunked_forward(A, Atil, Bm, Q, S0, chunk):
     return O, S
 
 
-def sig_delta_W(A, Bm):
-    """W of one chunk by the grid recursion of Theorem 3.4 (no inverse anywhere).
+def sig_delta_grid(X, A, Bm):
+    """Diagonal of the grid system of Theorem 3.4 with inhomogeneous term X (no inverse anywhere).
 
-    Column form as in the theorem: grid value W(t_m, t_k) in R^{dk x R}, m <= k.
-    Returns W in row form [n, dk]."""
+    X = A gives W; X = Atil gives U, which solves the same implicit equation with Atil in place of
+    the leading A (discrete flow of Section 3.1: U_k = Atil_k + sum_{m<k} U_m B_m^T A_k), so every
+    step of the theorem's proof goes through with Y(t_0, t_k) = X_k.
+    Column form as in the theorem: grid value Y(t_m, t_k) in R^{dx x R}, m <= k.
+    Returns the diagonal in row form [n, dx]."""
     L, R, dk = A.shape
+    dx = X.shape[2]
+    Xt = [X[k].T for k in range(L)]     # dx x R
     At = [A[k].T for k in range(L)]     # dk x R
     Bt = [Bm[k].T for k in range(L)]    # dk x R
-    G = [[None] * L for _ in range(L)]  # G[m][k] = W(t_m, t_k)
+    G = [[None] * L for _ in range(L)]  # G[m][k] = Y(t_m, t_k)
     for k in range(L):
-        G[0][k] = At[k].copy()
+        G[0][k] = Xt[k].copy()
     for k in range(L - 1):
         for m in range(k):
             G[m + 1][k + 1] = (G[m][k + 1] + G[m + 1][k] - G[m][k]
                                + G[m][m] @ (Bt[m].T @ (At[k + 1] - At[k])))
         G[k + 1][k + 1] = G[k][k + 1] + G[k][k] @ (Bt[k].T @ At[k + 1])
-    return np.stack([G[k][k].T for k in range(L)]).reshape(L * R, dk)
+    return np.stack([G[k][k].T for k in range(L)]).reshape(L * R, dx)
+
+
+def sig_delta_W(A, Bm):
+    """W of one chunk by the grid recursion of Theorem 3.4.  Returns W in row form [n, dk]."""
+    return sig_delta_grid(A, A, Bm)
 
 
 def propagator_from_flow(W, Bm):

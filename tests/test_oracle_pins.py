@@ -233,8 +233,20 @@ def test_signature_grid_recursion_gives_same_W(oracle, R):
     L, dk = 9, 4
     A = 0.5 * rng.standard_normal((L, R, dk))
     Bm = rng.standard_normal((L, R, dk))
-    W, _ = cf.chunk_flow(A, np.zeros((L, R, 2)), Bm)
+    At = rng.standard_normal((L, R, 3))
+    W, U = cf.chunk_flow(A, At, Bm)
     np.testing.assert_allclose(cf.sig_delta_W(A, Bm), W, atol=1e-10)
+    # the same grid with Atil as inhomogeneous term gives U (it solves the same implicit equation)
+    np.testing.assert_allclose(cf.sig_delta_grid(At, A, Bm), U, atol=1e-10)
+    # and both satisfy that implicit equation, written out token by token
+    for k in range(L):
+        acc_w, acc_u = A[k].T.copy(), At[k].T.copy()
+        for m in range(k):
+            coef = Bm[m] @ A[k].T                                  # B_m^T A_k, R x R
+            acc_w += W[m * R:(m + 1) * R].T @ coef
+            acc_u += U[m * R:(m + 1) * R].T @ coef
+        np.testing.assert_allclose(W[k * R:(k + 1) * R].T, acc_w, atol=1e-10)
+        np.testing.assert_allclose(U[k * R:(k + 1) * R].T, acc_u, atol=1e-10)
 
 
 # ---------------------------------------------------------------- P9 orthonormal keys
