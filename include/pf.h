@@ -183,6 +183,32 @@ pf_status pf_delta_chunk_scan(const void *Q, const void *K, const void *V, const
                               int B, int H, int L, int d_k, int d_v, int r, int chunk,
                               pf_stream stream);
 
+/*
+ * Step 2 of Section 3 by the paper's second construction (Theorem 3.4): W and U of every chunk
+ * from the grid recursion W(t_m, t_k) swept along its anti-diagonals, whose cells do not depend on
+ * each other; no triangular inverse is formed.  Delta variables as everywhere (A = beta k,
+ * Atil = -beta v, B = -k); U obeys the same recursion with Atil as the inhomogeneous term
+ * (discrete flow of Section 3.1).  Both dtypes; r in {1, 2, 4}; chunk <= 128; d_k and d_v multiples
+ * of 16 (else PF_ERR_UNSUPPORTED, see pf_delta_chunk_sigdelta_supported).  L need not be a
+ * multiple of chunk: the last chunk of a head is then shorter.
+ *
+ *   K, V, beta   as in pf_delta_fwd                                              in
+ *   W     [B, H, L, r, d_k]   fp32   out  rows (t, j) of W = (Id - M (.) A B^T)^{-1} A of t's chunk
+ *   U     [B, H, L, r, d_v]   fp32   out  rows (t, j) of U = (Id - M (.) A B^T)^{-1} Atil
+ *   workspace / workspace_bytes      device scratch of at least
+ *                                    pf_delta_chunk_sigdelta_workspace_bytes(...) bytes (the
+ *                                    (chunk r)^2 fp32 Gram B^T A of every chunk); overwritten.
+ *
+ * With these, S_1 = S_0 + (U + W S_0^T)^T B (Theorem 3.2).  The arithmetic is fp32 on the vector
+ * ALUs (the Gram of bf16 inputs on MFMA); this entry point exists to measure the construction
+ * against the blocked substitution behind pf_delta_chunk_flow and is not used by pf_delta_fwd.
+ */
+int pf_delta_chunk_sigdelta_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt);
+size_t pf_delta_chunk_sigdelta_workspace_bytes(int B, int H, int L, int r, int chunk);
+pf_status pf_delta_chunk_sigdelta(const void *K, const void *V, const void *beta, float *W, float *U,
+                                  int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt,
+                                  void *workspace, size_t workspace_bytes, pf_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -14,7 +14,8 @@ PF_OK, PF_ERR_NULL, PF_ERR_SHAPE, PF_ERR_UNSUPPORTED, PF_ERR_ALIGN, PF_ERR_WORKS
 PF_F32, PF_BF16 = 0, 1
 
 EXPORTS = ["pf_version", "pf_status_str", "pf_delta_fwd_supported", "pf_delta_fwd_block", "pf_delta_fwd_workspace_bytes",
-           "pf_delta_fwd", "pf_flow_fwd_supported", "pf_flow_fwd", "pf_delta_chunk_flow", "pf_delta_chunk_scan"]
+           "pf_delta_fwd", "pf_flow_fwd_supported", "pf_flow_fwd", "pf_delta_chunk_flow", "pf_delta_chunk_scan",
+           "pf_delta_chunk_sigdelta_supported", "pf_delta_chunk_sigdelta_workspace_bytes", "pf_delta_chunk_sigdelta"]
 
 
 class PfError(RuntimeError):
@@ -49,6 +50,12 @@ def _load() -> ctypes.CDLL:
     lib.pf_delta_chunk_flow.argtypes = [vp] * 5 + [i] * 7 + [vp]
     lib.pf_delta_chunk_scan.restype = i
     lib.pf_delta_chunk_scan.argtypes = [vp] * 9 + [i] * 7 + [vp]
+    lib.pf_delta_chunk_sigdelta_supported.restype = i
+    lib.pf_delta_chunk_sigdelta_supported.argtypes = [i] * 5
+    lib.pf_delta_chunk_sigdelta_workspace_bytes.restype = sz
+    lib.pf_delta_chunk_sigdelta_workspace_bytes.argtypes = [i] * 5
+    lib.pf_delta_chunk_sigdelta.restype = i
+    lib.pf_delta_chunk_sigdelta.argtypes = [vp] * 5 + [i] * 8 + [vp, sz, vp]
     return lib
 
 
@@ -120,6 +127,21 @@ def pf_delta_chunk_scan(Q, K, V, beta, Tt, Pt, S0, O, S_L, B, H, L, d_k, d_v, r,
     return int(_lib.pf_delta_chunk_scan(_ptr(Q), _ptr(K), _ptr(V), _ptr(beta), _ptr(Tt), _ptr(Pt), _ptr(S0),
                                         _ptr(O), _ptr(S_L), B, H, L, d_k, d_v, r, chunk,
                                         _stream_handle(stream)))
+
+
+def pf_delta_chunk_sigdelta_supported(d_k, d_v, r, chunk, dt) -> int:
+    return int(_lib.pf_delta_chunk_sigdelta_supported(d_k, d_v, r, chunk, dt))
+
+
+def pf_delta_chunk_sigdelta_workspace_bytes(B, H, L, r, chunk) -> int:
+    return int(_lib.pf_delta_chunk_sigdelta_workspace_bytes(B, H, L, r, chunk))
+
+
+def pf_delta_chunk_sigdelta(K, V, beta, W, U, B, H, L, d_k, d_v, r, chunk, dt, workspace, workspace_bytes,
+                            stream=None) -> int:
+    return int(_lib.pf_delta_chunk_sigdelta(_ptr(K), _ptr(V), _ptr(beta), _ptr(W), _ptr(U), B, H, L, d_k, d_v,
+                                            r, chunk, dt, _ptr(workspace), workspace_bytes,
+                                            _stream_handle(stream)))
 
 
 def delta_fwd(Q, K, V, beta, S0=None, *, chunk: int, workspace=None, stream=None):

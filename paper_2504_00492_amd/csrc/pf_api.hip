@@ -258,4 +258,35 @@ pf_status pf_delta_chunk_scan(const void *Q, const void *K, const void *V, const
     return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
 }
 
+int pf_delta_chunk_sigdelta_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt)
+{
+    if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return 0;
+    if (dt != PF_F32 && dt != PF_BF16) return 0;
+    return pf::sigdelta_supported(d_k, d_v, r, chunk) ? 1 : 0;
+}
+
+size_t pf_delta_chunk_sigdelta_workspace_bytes(int B, int H, int L, int r, int chunk)
+{
+    if (B <= 0 || H <= 0 || L <= 0 || r <= 0 || chunk <= 0 || (long long)B * H > 0x7fffffffLL) return 0;
+    return pf::sigdelta_workspace_bytes(B * H, L, r, chunk);
+}
+
+pf_status pf_delta_chunk_sigdelta(const void *K, const void *V, const void *beta, float *W, float *U,
+                                  int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt,
+                                  void *workspace, size_t workspace_bytes, pf_stream stream)
+{
+    if (L != 0 && (!K || !V || !beta || !W || !U)) return PF_ERR_NULL;
+    pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
+    if (st != PF_OK) return st;
+    if (!pf_delta_chunk_sigdelta_supported(d_k, d_v, r, chunk, dt)) return PF_ERR_UNSUPPORTED;
+    if (L == 0) return PF_OK;
+    if (!workspace || workspace_bytes < pf::sigdelta_workspace_bytes(B * H, L, r, chunk)) return PF_ERR_WORKSPACE;
+    if (!aligned16(K) || !aligned16(V) || !aligned16(beta) || !aligned16(W) || !aligned16(U) ||
+        !aligned16(workspace))
+        return PF_ERR_ALIGN;
+    hipError_t e = pf::launch_sigdelta(K, V, beta, W, U, static_cast<float *>(workspace), B * H, L, d_k, d_v, r,
+                                       chunk, dt == PF_BF16, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+}
+
 }  // extern "C"

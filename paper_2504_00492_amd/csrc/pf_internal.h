@@ -41,4 +41,11 @@ hipError_t launch_segment_constants(void *zeroV, float *ident, int n, int d, hip
 hipError_t launch_segment_compose(const float *S0, const float *Pseg, const float *Hseg, float *Sin,
                                   float *SL, int heads, int G, int d, hipStream_t stream);
 
+// ---- W, U of every chunk by the anti-diagonal sweep of Theorem 3.4 (pf_sigdelta.hip).  Gm is the
+// Gram workspace of sigdelta_workspace_bytes(); the last chunk of a head may be short.
+bool sigdelta_supported(int dk, int dv, int r, int chunk);
+size_t sigdelta_workspace_bytes(int heads, int L, int r, int chunk);
+hipError_t launch_sigdelta(const void *K, const void *V, const void *beta, float *W, float *U, float *Gm,
+                           int heads, int L, int dk, int dv, int r, int chunk, bool is_bf16, hipStream_t stream);
+
 }  // namespace pf
