@@ -75,6 +75,9 @@ def main():
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="after the timed region, run a plain device-to-device copy of this many MiB "
                          "(a kernel of known traffic to scale rocprofv3 FETCH_SIZE / WRITE_SIZE by)")
+    ap.add_argument("--compare-solvers", action="store_true",
+                    help="also time step 2 of Section 3 done by the anti-diagonal sweep of Theorem 3.4 "
+                         "(pf_delta_chunk_sigdelta) and report it next to the blocked substitution (flow kernel)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (one MI355X per box); "
@@ -198,6 +201,36 @@ def main():
         roofline = {"bound": "alu", "kernel": "generic_kernel", "achieved": tfl, "peak": PEAK_F32_VALU_TFLOPS,
                     "unit": "TFLOP/s", "frac": tfl / PEAK_F32_VALU_TFLOPS, "avg_kernel_ms": ms_per_step,
                     "traffic": None}
+    solvers = None
+    if args.compare_solvers and pf.pf_delta_chunk_sigdelta_supported(dk, dv, r, C, dt):
+        sneed = pf.pf_delta_chunk_sigdelta_workspace_bytes(B, H, L, r, C)
+        sws = torch.empty(sneed, dtype=torch.uint8, device=dev)
+        Wo = torch.empty((B, H, L, r, dk), dtype=torch.float32, device=dev)
+        Uo = torch.empty((B, H, L, r, dv), dtype=torch.float32, device=dev)
+        nrep = max(3, args.steps // 4)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(nrep)]
+        for i in range(1 + nrep):
+            if i >= 1:
+                evs[i - 1][0].record(stream)
+            st = pf.pf_delta_chunk_sigdelta(K, V, beta, Wo, Uo, B, H, L, dk, dv, r, C, dt, sws, sneed, stream)
+            assert st == pf.PF_OK, st
+            if i >= 1:
+                evs[i - 1][1].record(stream)
+        torch.cuda.synchronize()
+        t_sig = sum(a.elapsed_time(b) for a, b in evs) / nrep
+        n_sig = C * r
+        # useful fp32 operations of the sweep: C(C-1)/2 grid cells, r rows of d_k + d_v columns, 2 + r
+        # additions / multiply-adds each (counted as 2 flops), per chunk-head
+        sig_flops = (C * (C - 1) // 2) * r * (dk + dv) * (2 + r) * 2 * (token_heads / C)
+        solvers = {
+            "sigdelta": {"ms": t_sig, "chunk": C, "n": n_sig, "gives": "W, U fp32 (Gram kernel + sweep kernel)",
+                         "sweep_tflops_fp32": sig_flops / (t_sig * 1e-3) / 1e12,
+                         "frac_fp32_valu_peak": sig_flops / (t_sig * 1e-3) / 1e12 / PEAK_F32_VALU_TFLOPS},
+            "block_substitution": {"ms": kernels.get("flow_kernel", {}).get("ms"), "chunk": block, "n": block * r,
+                                   "gives": "T = (Id + G)^-1 and P, bf16 (W = T beta K and U are formed by "
+                                            "the scan kernel)"},
+        }
+        del sws, Wo, Uo
     traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(traffic_file):
         try:
@@ -232,6 +265,8 @@ def main():
         "cache_resident": bool(min_bytes + need + B * H * dv * dk * 4 < 256 * 2 ** 20) and nsets == 1,
         "input_sets_rotated": nsets,
     }
+    if solvers is not None:
+        out["solvers"] = solvers
 
     # ---- the oracle on the host cores, on a bounded sample of the same workload, plus parity on it
     if not args.no_cpu_baseline:
