@@ -180,3 +180,30 @@ def test_inputs_are_seeded_and_bf16_exact():
     assert 0.05 < frac < 0.15 and beta.max() <= 2.0
     w3 = synth.WORKLOADS["cfg3a"].with_(L=64)
     assert abs(float(np.std(synth.head_inputs(w3, 0)[4])) - 0.1) < 0.01
+
+
+def test_sigdelta_entry_checks(pf):
+    """pf_delta_chunk_sigdelta: instance table, workspace size and every check that returns before a launch."""
+    assert pf.pf_delta_chunk_sigdelta_supported(128, 128, 2, 64, pf.PF_BF16) == 1
+    assert pf.pf_delta_chunk_sigdelta_supported(16, 16, 1, 16, pf.PF_F32) == 1
+    assert pf.pf_delta_chunk_sigdelta_supported(128, 128, 3, 64, pf.PF_BF16) == 0      # r in {1, 2, 4}
+    assert pf.pf_delta_chunk_sigdelta_supported(128, 128, 2, 129, pf.PF_BF16) == 0     # chunk <= 128
+    assert pf.pf_delta_chunk_sigdelta_supported(24, 16, 2, 16, pf.PF_F32) == 0         # d multiple of 16
+    assert pf.pf_delta_chunk_sigdelta_supported(16, 16, 1, 16, 7) == 0
+    # one (chunk r)^2 fp32 Gram per chunk, the short last chunk included
+    assert pf.pf_delta_chunk_sigdelta_workspace_bytes(4, 16, 4096, 2, 64) == 64 * 64 * 128 * 128 * 4
+    assert pf.pf_delta_chunk_sigdelta_workspace_bytes(1, 2, 50, 2, 16) == 2 * 4 * 32 * 32 * 4
+    assert pf.pf_delta_chunk_sigdelta_workspace_bytes(1, 2, 0, 2, 16) == 0
+    p = 1 << 20   # fake, aligned, never dereferenced: every call below fails a check first
+    call = lambda K=p, W=p, L=64, r=1, ws=p, wb=1 << 30, dt=pf.PF_F32: pf.pf_delta_chunk_sigdelta(
+        K, p, p, W, p, 1, 1, L, 16, 16, r, 16, dt, ws, wb, 0)
+    assert call(K=None) == pf.PF_ERR_NULL
+    assert call(W=None) == pf.PF_ERR_NULL
+    assert call(L=-2) == pf.PF_ERR_SHAPE
+    assert call(r=3) == pf.PF_ERR_UNSUPPORTED
+    assert call(dt=5) == pf.PF_ERR_UNSUPPORTED
+    assert call(ws=None) == pf.PF_ERR_WORKSPACE
+    assert call(wb=100) == pf.PF_ERR_WORKSPACE
+    assert call(K=p + 2) == pf.PF_ERR_ALIGN
+    assert call(ws=p + 4) == pf.PF_ERR_ALIGN
+    assert call(L=0, K=None, W=None, ws=None, wb=0) == pf.PF_OK
