@@ -6,6 +6,8 @@ package imports nothing from the product package.
 
 * ``pf_oracle.c``      token-by-token recurrence (Section 1.1 recurrence/readout, Section 3.1
                        discretised dynamics, delta mapping of the Remark in Section 3.1), plain C.
+                       ``delta_product_fwd`` (product form of the rank-r transition, the contrast
+                       case) is that same routine on the sequence of L*r virtual tokens.
 * ``chunk_flow_ref.py`` numpy fp64 transcription of the chunk flow (Theorem 3.2, Proposition 3.3,
                        Theorem 3.4); used by the tests only, to pin the recurrence from a second,
                        independent direction.
@@ -117,3 +119,29 @@ def delta_fwd(Q, K, V, beta, S0=None, want_O=True, nthreads=0):
     if rc != 0:
         raise MemoryError("pf_oracle_delta_fwd")
     return O, SL
+
+
+def delta_product_fwd(Q, K, V, beta, S0=None, want_O=True, nthreads=0):
+    """Product form of the rank-r transition: the r (k, v, beta) triples of a token are applied one
+    after another, S <- S (I - beta k k^T) + beta v k^T for j = 0 .. r-1, and o_t = S q_t is read after
+    the r-th.  By definition this is the rank-1 delta rule (Section 1.3) over the L*r virtual tokens
+    in (t, j) order, read out at every r-th of them, so it is computed by ``delta_fwd`` on that
+    re-indexed sequence (queries of the other virtual tokens are zero and their outputs dropped).
+    Shapes as for ``delta_fwd``."""
+    K = np.ascontiguousarray(K, dtype=np.float32)
+    V = np.ascontiguousarray(V, dtype=np.float32)
+    Q = np.ascontiguousarray(Q, dtype=np.float32)
+    beta = np.ascontiguousarray(beta, dtype=np.float32)
+    lead = K.shape[:-3]
+    L, R, dk = K.shape[-3:]
+    dv = V.shape[-1]
+    Kv = K.reshape(lead + (L * R, 1, dk))
+    Vv = V.reshape(lead + (L * R, 1, dv))
+    bv = beta.reshape(lead + (L * R, 1))
+    Qv = np.zeros(lead + (L, R, dk), dtype=np.float32)
+    Qv[..., R - 1, :] = Q
+    Qv = Qv.reshape(lead + (L * R, dk))
+    Ov, SL = delta_fwd(Qv, Kv, Vv, bv, S0, want_O=want_O, nthreads=nthreads)
+    if not want_O:
+        return None, SL
+    return np.ascontiguousarray(Ov.reshape(lead + (L, R, dv))[..., R - 1, :]), SL

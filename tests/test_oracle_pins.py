@@ -340,3 +340,47 @@ def test_empty_sequence(oracle):
     O, SL = oracle.flow_head(np.zeros((0, 1, dk)), np.zeros((0, 1, dv)), np.zeros((0, 1, dk)),
                              np.zeros((0, dk)), S0)
     assert O.shape == (0, dv) and np.array_equal(SL, S0)
+
+
+# ---------------------------------------------------------------- product form (contrast case)
+def test_product_form_is_the_ordered_product_of_rank_one_factors(oracle):
+    """The product-form oracle against the definition written out in numpy: per token r factors
+    (I - beta k k^T) applied left to right, each with its own input term; readout after the last."""
+    rng = np.random.default_rng(90)
+    L, r, dk, dv = 6, 3, 5, 4
+    Q, K, V, beta, S0 = _rand_delta(rng, L, r, dk, dv, beta_hi=2.0)
+    O, SL = oracle.delta_product_fwd(Q, K, V, beta, S0)
+    K32, V32, Q32, b32, S032 = (np.asarray(x, dtype=np.float32).astype(np.float64) for x in (K, V, Q, beta, S0))
+    S = S032.copy()
+    for t in range(L):
+        for j in range(r):
+            k, v, b = K32[t, j], V32[t, j], b32[t, j]
+            S = S @ (np.eye(dk) - b * np.outer(k, k)) + b * np.outer(v, k)
+        np.testing.assert_allclose(O[t], S @ Q32[t], atol=1e-12)
+    np.testing.assert_allclose(SL, S, atol=1e-12)
+
+
+def test_product_form_against_additive_form(oracle):
+    """r = 1: the two forms are the same recurrence.  Keys of one token mutually orthogonal: the
+    factors commute and their product is I - sum beta k k^T, and each input term passes the later
+    factors unchanged, so the forms agree.  Correlated keys: they differ (the contrast is real)."""
+    rng = np.random.default_rng(91)
+    L, dk, dv = 5, 6, 3
+    Q, K, V, beta, S0 = _rand_delta(rng, L, 1, dk, dv)
+    Oa, Sa = oracle.delta_fwd(Q, K, V, beta, S0)
+    Op, Sp = oracle.delta_product_fwd(Q, K, V, beta, S0)
+    np.testing.assert_allclose(Op, Oa, atol=1e-12)
+    np.testing.assert_allclose(Sp, Sa, atol=1e-12)
+    r = 2
+    Q, K, V, beta, S0 = _rand_delta(rng, L, r, dk, dv)
+    for t in range(L):                                   # orthonormalise the two keys of each token
+        K[t] = np.linalg.qr(K[t].T)[0].T
+    K = K.astype(np.float32).astype(np.float64)
+    Oa, Sa = oracle.delta_fwd(Q, K, V, beta, S0)
+    Op, Sp = oracle.delta_product_fwd(Q, K, V, beta, S0)
+    np.testing.assert_allclose(Op, Oa, atol=1e-5)        # keys orthogonal up to the fp32 rounding of K
+    np.testing.assert_allclose(Sp, Sa, atol=1e-5)
+    Q, K, V, beta, S0 = _rand_delta(rng, L, r, dk, dv)   # generic (correlated) keys
+    _, Sa = oracle.delta_fwd(Q, K, V, beta, S0)
+    _, Sp = oracle.delta_product_fwd(Q, K, V, beta, S0)
+    assert np.abs(Sa - Sp).max() > 1e-3
