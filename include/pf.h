@@ -118,6 +118,25 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
                        void *workspace, size_t workspace_bytes, pf_stream stream);
 
 /*
+ * Product form of the rank-r transition (the DeltaProduct-style reading that Section 1 cites, as
+ * opposed to the additive rank-r increment of Section 3.1 that pf_delta_fwd computes): the r
+ * (k, v, beta) triples of a token are applied one after another,
+ *
+ *     S <- S (I - beta_{t,j} k_{t,j} k_{t,j}^T) + beta_{t,j} v_{t,j} k_{t,j}^T     j = 0 .. r-1,
+ *     o_t = S_t q_t   after the r-th,
+ *
+ * i.e. the rank-1 delta rule of Section 1.3 over the L*r virtual tokens, read out at every r-th.
+ * Same chunk flow with one change: the mask M of Theorem 3.2 is strict in the virtual token instead
+ * of strict in time (the readout mask is unchanged).  Arguments, workspace size
+ * (pf_delta_fwd_workspace_bytes), kernel families (pf_delta_fwd_supported) and error behaviour are
+ * those of pf_delta_fwd.  For r = 1 the two entry points compute the same thing.
+ */
+pf_status pf_delta_product_fwd(const void *Q, const void *K, const void *V, const void *beta,
+                               const float *S0, void *O, float *S_L,
+                               int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt,
+                               void *workspace, size_t workspace_bytes, pf_stream stream);
+
+/*
  * The same chunked forward for general low-rank drivers (Section 3.1, before the delta mapping
  * of its Remark): per (b, h), with A_t, B_t in R^{d_k x r} and Atil_t in R^{d_v x r} stored by
  * column,

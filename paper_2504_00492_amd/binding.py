@@ -14,7 +14,7 @@ PF_OK, PF_ERR_NULL, PF_ERR_SHAPE, PF_ERR_UNSUPPORTED, PF_ERR_ALIGN, PF_ERR_WORKS
 PF_F32, PF_BF16 = 0, 1
 
 EXPORTS = ["pf_version", "pf_status_str", "pf_delta_fwd_supported", "pf_delta_fwd_block", "pf_delta_fwd_workspace_bytes",
-           "pf_delta_fwd", "pf_flow_fwd_supported", "pf_flow_fwd", "pf_delta_chunk_flow", "pf_delta_chunk_scan",
+           "pf_delta_fwd", "pf_delta_product_fwd", "pf_flow_fwd_supported", "pf_flow_fwd", "pf_delta_chunk_flow", "pf_delta_chunk_scan",
            "pf_delta_chunk_sigdelta_supported", "pf_delta_chunk_sigdelta_workspace_bytes", "pf_delta_chunk_sigdelta"]
 
 
@@ -42,6 +42,8 @@ def _load() -> ctypes.CDLL:
     lib.pf_delta_fwd_workspace_bytes.argtypes = [i] * 8
     lib.pf_delta_fwd.restype = i
     lib.pf_delta_fwd.argtypes = [vp] * 7 + [i] * 8 + [vp, sz, vp]
+    lib.pf_delta_product_fwd.restype = i
+    lib.pf_delta_product_fwd.argtypes = [vp] * 7 + [i] * 8 + [vp, sz, vp]
     lib.pf_flow_fwd_supported.restype = i
     lib.pf_flow_fwd_supported.argtypes = [i, i, i, i, i]
     lib.pf_flow_fwd.restype = i
@@ -108,6 +110,14 @@ def pf_delta_fwd(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, wor
                                  _stream_handle(stream)))
 
 
+def pf_delta_product_fwd(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, workspace, workspace_bytes,
+                         stream=None) -> int:
+    """Raw call; returns the pf_status.  Pointers may be torch tensors, ints or None."""
+    return int(_lib.pf_delta_product_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(beta), _ptr(S0), _ptr(O), _ptr(S_L),
+                                         B, H, L, d_k, d_v, r, chunk, dt, _ptr(workspace), workspace_bytes,
+                                         _stream_handle(stream)))
+
+
 def pf_flow_fwd_supported(d_k, d_v, r, chunk, dt) -> int:
     return int(_lib.pf_flow_fwd_supported(d_k, d_v, r, chunk, dt))
 
@@ -144,8 +154,8 @@ def pf_delta_chunk_sigdelta(K, V, beta, W, U, B, H, L, d_k, d_v, r, chunk, dt, w
                                             _stream_handle(stream)))
 
 
-def delta_fwd(Q, K, V, beta, S0=None, *, chunk: int, workspace=None, stream=None):
-    """Convenience wrapper over pf_delta_fwd for torch CUDA tensors.
+def delta_fwd(Q, K, V, beta, S0=None, *, chunk: int, workspace=None, stream=None, product: bool = False):
+    """Convenience wrapper over pf_delta_fwd (pf_delta_product_fwd with product=True) for torch CUDA tensors.
 
     Q [B,H,L,dk], K [B,H,L,r,dk], V [B,H,L,r,dv], beta [B,H,L,r] (float32 or bfloat16, contiguous),
     S0 [B,H,dv,dk] float32 or None.  Allocates O, S_L (and the workspace unless given) with torch,
@@ -176,9 +186,10 @@ def delta_fwd(Q, K, V, beta, S0=None, *, chunk: int, workspace=None, stream=None
     if workspace is None and need > 0:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    st = pf_delta_fwd(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, workspace, wbytes, stream)
+    call = pf_delta_product_fwd if product else pf_delta_fwd
+    st = call(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, workspace, wbytes, stream)
     if st != PF_OK:
-        raise PfError(st, "pf_delta_fwd")
+        raise PfError(st, call.__name__)
     return O, S_L
 
 

@@ -134,9 +134,10 @@ size_t pf_delta_fwd_workspace_bytes(int B, int H, int L, int d_k, int d_v, int r
     return plan_workspace(B * H, L, d_k, r, block).total;
 }
 
-pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
-                       void *O, float *S_L, int B, int H, int L, int d_k, int d_v, int r, int chunk,
-                       pf_dtype dt, void *workspace, size_t workspace_bytes, pf_stream stream)
+static pf_status delta_fwd_impl(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
+                                void *O, float *S_L, int B, int H, int L, int d_k, int d_v, int r, int chunk,
+                                pf_dtype dt, void *workspace, size_t workspace_bytes, pf_stream stream,
+                                bool product)
 {
     if (L != 0 && (!Q || !K || !V || !beta || !O)) return PF_ERR_NULL;
     pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
@@ -157,7 +158,7 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
     if (fam == 1 || L < block) {
         // generic family, an empty sequence, or a sequence shorter than one flow block
         hipError_t e = pf::launch_generic(Q, K, V, beta, S0, O, S_L, heads, L, d_k, d_v, r,
-                                          fam == 1 ? chunk : (tchunk ? tchunk : 1), dt == PF_BF16, s);
+                                          fam == 1 ? chunk : (tchunk ? tchunk : 1), dt == PF_BF16, s, 0, product);
         return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
     }
     const WorkspacePlan wp = plan_workspace(heads, L, d_k, r, block);
@@ -168,7 +169,7 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
     {
         float *Smid = tail ? reinterpret_cast<float *>(ws + wp.oS) : S_L;
         const void *Tt = ws + wp.oT, *Pt = ws + wp.oP;
-        hipError_t e = pf::launch_chunk_flow(Q, K, beta, ws + wp.oT, ws + wp.oP, heads, L, d_k, r, block, s);
+        hipError_t e = pf::launch_chunk_flow(Q, K, beta, ws + wp.oT, ws + wp.oP, heads, L, d_k, r, block, s, product);
         if (e != hipSuccess) return PF_ERR_LAUNCH;
         if (wp.segments > 1) {
             // Segment-parallel scan (no tail here): every segment of every head is a chain of
@@ -195,10 +196,26 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
     }
     if (tail) {
         hipError_t e = pf::launch_generic(Q, K, V, beta, state, O, S_L, heads, L, d_k, d_v, r, tchunk, true, s,
-                                          L - tail);
+                                          L - tail, product);
         if (e != hipSuccess) return PF_ERR_LAUNCH;
     }
     return PF_OK;
+}
+
+pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
+                       void *O, float *S_L, int B, int H, int L, int d_k, int d_v, int r, int chunk,
+                       pf_dtype dt, void *workspace, size_t workspace_bytes, pf_stream stream)
+{
+    return delta_fwd_impl(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, workspace, workspace_bytes,
+                          stream, false);
+}
+
+pf_status pf_delta_product_fwd(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
+                               void *O, float *S_L, int B, int H, int L, int d_k, int d_v, int r, int chunk,
+                               pf_dtype dt, void *workspace, size_t workspace_bytes, pf_stream stream)
+{
+    return delta_fwd_impl(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, workspace, workspace_bytes,
+                          stream, true);
 }
 
 int pf_flow_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt)

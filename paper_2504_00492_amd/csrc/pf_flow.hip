@@ -64,7 +64,7 @@ struct FlowLds {
 template <int D, int N, int C>
 __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
     const bf16 *__restrict__ Q, const bf16 *__restrict__ K, const bf16 *__restrict__ beta,
-    bf16 *__restrict__ Tt, bf16 *__restrict__ Pt, int nchunks, int NC, int tail)
+    bf16 *__restrict__ Tt, bf16 *__restrict__ Pt, int nchunks, int NC, int tail, int mask_shift)
 {
     using Ld = FlowLds<D, N, C>;
     constexpr int R = N / C;          // rank: virtual tokens per token
@@ -171,7 +171,10 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
                     for (int jj = 0; jj < 4; ++jj) {
                         const int row = 16 * mi + 4 * g + jj, col = 16 * ni + r16;
                         float val = 0.0f;
-                        if (tile != 1 && (col / R < row / R))
+                        // strict in time: rows and columns compared by token, i.e. by virtual
+                        // token >> log2(R); mask_shift = 0 compares virtual tokens themselves
+                        // (the r sub-updates of a token then see each other, one after another)
+                        if (tile != 1 && ((col >> mask_shift) < (row >> mask_shift)))
                             val = acc[tile == 0 ? 0 : tile - 1][jj] * bs[32 * db + row];
                         Ns[row * NP + col] = val;
                     }
@@ -371,9 +374,12 @@ bool mfma_instance_exists(int d, int n, int chunk)
 
 template <int D, int N, int C>
 static hipError_t launch_flow_instance(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,
-                                       size_t nchunks, int NC, int tail, hipStream_t stream)
+                                       size_t nchunks, int NC, int tail, bool product, hipStream_t stream)
 {
     auto kern = flow_kernel<D, N, C>;
+    int mask_shift = 0;
+    if (!product)
+        while ((1 << mask_shift) < N / C) ++mask_shift;
     constexpr size_t lds = FlowLds<D, N, C>::total;
     static_assert(lds <= kMaxLdsBytes, "flow kernel LDS plan exceeds the CU");
     // the LDS opt-in is per device and sticks: ask once per device, not once per launch
@@ -393,12 +399,12 @@ static hipError_t launch_flow_instance(const void *Q, const void *K, const void 
     const size_t resident = kNumCUs * (per_cu > 2 ? 2 : per_cu);
     const unsigned grid = (unsigned)(nchunks < resident ? nchunks : resident);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kFlowThreads), lds, stream, (const bf16 *)Q,
-                       (const bf16 *)K, (const bf16 *)beta, (bf16 *)Tt, (bf16 *)Pt, (int)nchunks, NC, tail);
+                       (const bf16 *)K, (const bf16 *)beta, (bf16 *)Tt, (bf16 *)Pt, (int)nchunks, NC, tail, mask_shift);
     return hipGetLastError();
 }
 
 hipError_t launch_chunk_flow(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,
-                             int heads, int L, int d, int r, int chunk, hipStream_t stream)
+                             int heads, int L, int d, int r, int chunk, hipStream_t stream, bool product)
 {
     const int NC = L / chunk, tail = L % chunk;   // the tail tokens of every head are skipped
     const size_t nchunks = (size_t)heads * NC;
@@ -407,7 +413,7 @@ hipError_t launch_chunk_flow(const void *Q, const void *K, const void *beta, voi
     const int n = chunk * r;
 #define X(DD, NN, CC)                                                                        \
     if (d == DD && n == NN && chunk == CC)                                                    \
-        return launch_flow_instance<DD, NN, CC>(Q, K, beta, Tt, Pt, nchunks, NC, tail, stream);
+        return launch_flow_instance<DD, NN, CC>(Q, K, beta, Tt, Pt, nchunks, NC, tail, product, stream);
     PF_FLOW_INSTANCES(X)
 #undef X
     return hipErrorInvalidValue;

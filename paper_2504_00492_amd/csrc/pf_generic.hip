@@ -56,13 +56,18 @@ __host__ __device__ inline GenericPlan generic_plan(int dk, int dv, int r, int c
     return p;
 }
 
+// rs = rows of the system that are solved together and do not see each other: r for the paper's
+// additive rank-r increment (Theorem 3.2's mask, strict in time), 1 for the product form, in
+// which the r sub-updates of a token are applied one after another (mask strict in the virtual
+// token).  The readout mask is the same in both.
 // kDrivers == false: (K, V, beta) are keys, values, betas of the delta rule.
 // kDrivers == true:  (K, V, beta) are (B, Atil, A) of the general recurrence (beta: [.., r, d_k]).
 template <typename T, bool kDrivers>
 __global__ __launch_bounds__(256) void generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                       const T *__restrict__ V, const T *__restrict__ beta,
                                                       const float *S0, T *__restrict__ O, float *SL,
-                                                      int L, int dk, int dv, int r, int chunk, int t0)
+                                                      int L, int dk, int dv, int r, int chunk, int t0,
+                                                      int rs)
 {
     extern __shared__ float smem[];
     const GenericPlan pl = generic_plan(dk, dv, r, chunk);
@@ -112,7 +117,7 @@ __global__ __launch_bounds__(256) void generic_kernel(const T *__restrict__ Q, c
         for (int i = tid; i < n * n; i += nth) {
             const int row = i / n, col = i % n;
             float acc = 0.0f;
-            if (col / r < row / r)
+            if (col / rs < row / rs)
                 for (int x = 0; x < dk; ++x) acc = fmaf(Wc[row * ldk + x], Kc[col * ldk + x], acc);
             G[row * ldn + col] = acc;
         }
@@ -124,18 +129,18 @@ __global__ __launch_bounds__(256) void generic_kernel(const T *__restrict__ Q, c
             Pm[t * ldn + col] = acc;
         }
         __syncthreads();
-        // ---- forward substitution, one token (r rows) at a time
+        // ---- forward substitution, rs rows at a time (one token, or one virtual token)
         const int ncol = dk + dv;
-        for (int t = 1; t < cl; ++t) {
-            for (int i = tid; i < r * ncol; i += nth) {
-                const int row = t * r + i / ncol, col = i % ncol;
+        for (int t = 1; t < n / rs; ++t) {
+            for (int i = tid; i < rs * ncol; i += nth) {
+                const int row = t * rs + i / ncol, col = i % ncol;
                 float acc = 0.0f;
                 if (col < dk) {
-                    for (int j = 0; j < t * r; ++j) acc = fmaf(G[row * ldn + j], Wc[j * ldk + col], acc);
+                    for (int j = 0; j < t * rs; ++j) acc = fmaf(G[row * ldn + j], Wc[j * ldk + col], acc);
                     Wc[row * ldk + col] -= acc;
                 } else {
                     const int m = col - dk;
-                    for (int j = 0; j < t * r; ++j) acc = fmaf(G[row * ldn + j], Uc[j * ldv + m], acc);
+                    for (int j = 0; j < t * rs; ++j) acc = fmaf(G[row * ldn + j], Uc[j * ldv + m], acc);
                     Uc[row * ldv + m] -= acc;
                 }
             }
@@ -179,7 +184,7 @@ size_t generic_lds_bytes(int dk, int dv, int r, int chunk)
 template <typename T, bool kDrivers>
 static hipError_t launch_generic_instance(const void *Q, const void *K, const void *V, const void *beta,
                                           const float *S0, void *O, float *SL, int heads, int L, int dk, int dv,
-                                          int r, int chunk, int t0, hipStream_t stream)
+                                          int r, int chunk, int t0, bool product, hipStream_t stream)
 {
     const size_t lds = generic_lds_bytes(dk, dv, r, chunk);
     auto kern = generic_kernel<T, kDrivers>;
@@ -187,24 +192,24 @@ static hipError_t launch_generic_instance(const void *Q, const void *K, const vo
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(heads), dim3(256), lds, stream, (const T *)Q, (const T *)K, (const T *)V,
-                       (const T *)beta, S0, (T *)O, SL, L, dk, dv, r, chunk, t0);
+                       (const T *)beta, S0, (T *)O, SL, L, dk, dv, r, chunk, t0, product ? 1 : r);
     return hipGetLastError();
 }
 
 hipError_t launch_generic(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
                           void *O, float *SL, int heads, int L, int dk, int dv, int r, int chunk,
-                          bool is_bf16, hipStream_t stream, int t0)
+                          bool is_bf16, hipStream_t stream, int t0, bool product)
 {
-    return is_bf16 ? launch_generic_instance<uint16_t, false>(Q, K, V, beta, S0, O, SL, heads, L, dk, dv, r, chunk, t0, stream)
-                   : launch_generic_instance<float, false>(Q, K, V, beta, S0, O, SL, heads, L, dk, dv, r, chunk, t0, stream);
+    return is_bf16 ? launch_generic_instance<uint16_t, false>(Q, K, V, beta, S0, O, SL, heads, L, dk, dv, r, chunk, t0, product, stream)
+                   : launch_generic_instance<float, false>(Q, K, V, beta, S0, O, SL, heads, L, dk, dv, r, chunk, t0, product, stream);
 }
 
 hipError_t launch_generic_drivers(const void *Q, const void *A, const void *Atil, const void *Bm, const float *S0,
                                   void *O, float *SL, int heads, int L, int dk, int dv, int r, int chunk,
                                   bool is_bf16, hipStream_t stream)
 {
-    return is_bf16 ? launch_generic_instance<uint16_t, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, 0, stream)
-                   : launch_generic_instance<float, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, 0, stream);
+    return is_bf16 ? launch_generic_instance<uint16_t, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, 0, false, stream)
+                   : launch_generic_instance<float, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, 0, false, stream);
 }
 
 }  // namespace pf

@@ -15,7 +15,9 @@ size_t generic_lds_bytes(int dk, int dv, int r, int chunk);
 // tokens [t0, L) of every head; the heads are L tokens apart in memory
 hipError_t launch_generic(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
                           void *O, float *SL, int heads, int L, int dk, int dv, int r, int chunk,
-                          bool is_bf16, hipStream_t stream, int t0 = 0);
+                          bool is_bf16, hipStream_t stream, int t0 = 0, bool product = false);
+// (product: the r sub-updates of a token are applied one after another instead of as one additive
+// rank-r increment; the solve mask is then strict in the virtual token.  Same flag below.)
 // general drivers (A, Atil, B) of Section 3.1 through the same kernel
 hipError_t launch_generic_drivers(const void *Q, const void *A, const void *Atil, const void *Bm,
                                   const float *S0, void *O, float *SL, int heads, int L, int dk, int dv,
@@ -25,7 +27,8 @@ hipError_t launch_generic_drivers(const void *Q, const void *A, const void *Atil
 // the first L / chunk whole blocks of every head (heads L tokens apart) and leave the tail alone.
 bool mfma_instance_exists(int d, int n, int chunk);
 hipError_t launch_chunk_flow(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,
-                             int heads, int L, int d, int r, int chunk, hipStream_t stream);
+                             int heads, int L, int d, int r, int chunk, hipStream_t stream,
+                             bool product = false);
 hipError_t launch_chunk_scan(const void *Q, const void *K, const void *V, const void *beta,
                              const void *Tt, const void *Pt, const float *S0, void *O, float *SL,
                              int heads, int L, int d, int r, int chunk, hipStream_t stream,

@@ -103,10 +103,18 @@ def test_argument_checks_return_before_launch(pf):
     BF = pf.PF_BF16
     dims = dict(B=1, H=1, L=128, d_k=128, d_v=128, r=2, chunk=64)
 
-    def call(Q=A, K=A, V=A, beta=A, S0=A, O=A, SL=A, ws=A, wb=1 << 40, dt=BF, **kw):
+    def call(Q=A, K=A, V=A, beta=A, S0=A, O=A, SL=A, ws=A, wb=1 << 40, dt=BF, fn=pf.pf_delta_fwd, **kw):
         d = dict(dims, **kw)
-        return pf.pf_delta_fwd(Q, K, V, beta, S0, O, SL, d["B"], d["H"], d["L"], d["d_k"], d["d_v"], d["r"],
-                               d["chunk"], dt, ws, wb, 0)
+        return fn(Q, K, V, beta, S0, O, SL, d["B"], d["H"], d["L"], d["d_k"], d["d_v"], d["r"],
+                  d["chunk"], dt, ws, wb, 0)
+
+    # the product-form entry point shares every check
+    prod = pf.pf_delta_product_fwd
+    assert call(fn=prod, V=None) == pf.PF_ERR_NULL
+    assert call(fn=prod, r=0) == pf.PF_ERR_SHAPE
+    assert call(fn=prod, dt=5) == pf.PF_ERR_UNSUPPORTED
+    assert call(fn=prod, O=A + 2) == pf.PF_ERR_ALIGN
+    assert call(fn=prod, wb=16) == pf.PF_ERR_WORKSPACE
 
     assert call(Q=None) == pf.PF_ERR_NULL
     assert call(K=None) == pf.PF_ERR_NULL
