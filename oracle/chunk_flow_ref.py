@@ -147,3 +147,20 @@ def propagator_from_flow(W, Bm):
     Proposition 3.1 and P = Id + int P dw of Proposition 2.1).  Returns dk x dk."""
     n, dk = W.shape
     return np.eye(dk) + W.T @ Bm.reshape(n, dk)
+
+
+def exp_rank1_beta(K, beta):
+    """Step size that makes a rank-1 delta step the exact flow of its increment (Section 3.3).
+
+    For rank-1 increments the exponential of Section 3.3 has the closed form
+    exp(a b^T) = Id + phi(<b, a>) a b^T with phi(x) = (e^x - 1) / x.  Under the delta mapping
+    (a = beta k, b = -k) <b, a> = -beta |k|^2, so exp(d omega) = Id - beta_eff k k^T with
+    beta_eff = (1 - exp(-beta |k|^2)) / |k|^2.  The input increment, carried by the same flow over
+    the step (S' = S a b^T + atil b^T on [0, 1]), picks up the same factor phi, so the exact step is
+    the delta rule with beta_eff in place of beta.  |k| = 0 gives beta_eff = beta (phi(0) = 1).
+    K [..., dk], beta [...] -> beta_eff [...]."""
+    K = np.asarray(K, dtype=np.float64)
+    beta = np.asarray(beta, dtype=np.float64)
+    s = np.sum(K * K, axis=-1)
+    safe = np.where(s > 0, s, 1.0)
+    return np.where(s > 0, -np.expm1(-beta * safe) / safe, beta)

@@ -384,3 +384,39 @@ def test_product_form_against_additive_form(oracle):
     _, Sa = oracle.delta_fwd(Q, K, V, beta, S0)
     _, Sp = oracle.delta_product_fwd(Q, K, V, beta, S0)
     assert np.abs(Sa - Sp).max() > 1e-3
+
+
+# ---------------------------------------------------------------- Section 3.3, rank-1 exponential
+def test_exponential_step_matches_matrix_exponential(oracle):
+    """exp(a b^T) for the delta increment against scipy's expm, and the whole step (transition and
+    input) against the exact flow of S' = S a b^T + atil b^T over [0, 1], computed with expm of
+    the augmented generator.  Then the small-step limit and |k| = 0."""
+    from scipy.linalg import expm
+    rng = np.random.default_rng(95)
+    dk, dv = 5, 3
+    for beta in (0.05, 0.7, 1.9, 4.0):
+        k = rng.standard_normal(dk) * rng.uniform(0.3, 1.5)
+        v = rng.standard_normal(dv)
+        S0 = rng.standard_normal((dv, dk))
+        be = float(cf.exp_rank1_beta(k, beta))
+        a, b, at = beta * k, -k, -beta * v
+        np.testing.assert_allclose(expm(np.outer(a, b)), np.eye(dk) - be * np.outer(k, k), atol=1e-12)
+        # augmented system: [S 1] ' = [S 1] [[a b^T, 0], [atil b^T, 0]]  (row vectors, one row of S at a time)
+        gen = np.zeros((dk + dv, dk + dv))
+        gen[:dk, :dk] = np.outer(a, b)
+        gen[dk:, :dk] = np.outer(at, b)
+        E = expm(gen)
+        S1_exact = S0 @ E[:dk, :dk] + E[dk:, :dk]
+        S1_step = S0 @ (np.eye(dk) - be * np.outer(k, k)) + be * np.outer(v, k)
+        np.testing.assert_allclose(S1_step, S1_exact, atol=1e-12)
+        # the delta-rule oracle run with beta_eff is that exact step
+        _, SL = oracle.flow_head((be * k)[None, None], (-be * v)[None, None], (-k)[None, None],
+                                 np.zeros((1, dk)), S0)
+        np.testing.assert_allclose(SL, S1_exact, atol=1e-12)
+    k = rng.standard_normal(dk)
+    s = k @ k
+    np.testing.assert_allclose(cf.exp_rank1_beta(k, 1e-4), 1e-4 - 0.5e-8 * s, rtol=1e-6)   # Euler is the first order
+    assert cf.exp_rank1_beta(np.zeros(dk), 0.8) == 0.8
+    # unit keys: beta_eff = 1 - exp(-beta) stays below 1, whatever beta is (no reflection)
+    ku = k / np.linalg.norm(k)
+    np.testing.assert_allclose(cf.exp_rank1_beta(ku, np.array([0.5, 2.0, 50.0])), 1 - np.exp(-np.array([0.5, 2.0, 50.0])), rtol=1e-12)
