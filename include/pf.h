@@ -137,6 +137,27 @@ pf_status pf_delta_product_fwd(const void *Q, const void *K, const void *V, cons
                                void *workspace, size_t workspace_bytes, pf_stream stream);
 
 /*
+ * Step sizes of the exact rank-1 flow (Section 3.3, product of exponentials): for rank-1 increments
+ * exp(a b^T) = Id + ((e^x - 1) / x) a b^T with x = <b, a>; under the delta mapping x = -beta |k|^2, so
+ * the exact step over one (k, v, beta) is the delta-rule step with
+ *
+ *     beta_eff = (1 - exp(-beta |k|^2)) / |k|^2        (beta itself where k = 0)
+ *
+ * in place of beta, for the transition and for the input term alike (the input increment is
+ * carried by the same flow).  Feeding beta_eff to pf_delta_fwd with r = 1, or to pf_delta_product_fwd
+ * with any r, replaces the Euler discretisation of Section 3.1 by the exact exponential of every
+ * rank-1 increment.
+ *
+ *   K         [B, H, L, r, d_k]   dt   in
+ *   beta      [B, H, L, r]        dt   in
+ *   beta_out  [B, H, L, r]        dt   out   may be the same buffer as beta
+ *
+ * fp32 arithmetic; the result is rounded to dt.  Any d_k.  Error behaviour as for pf_delta_fwd.
+ */
+pf_status pf_beta_exponential(const void *K, const void *beta, void *beta_out,
+                              int B, int H, int L, int d_k, int r, pf_dtype dt, pf_stream stream);
+
+/*
  * The same chunked forward for general low-rank drivers (Section 3.1, before the delta mapping
  * of its Remark): per (b, h), with A_t, B_t in R^{d_k x r} and Atil_t in R^{d_v x r} stored by
  * column,

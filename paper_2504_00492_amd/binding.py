@@ -14,7 +14,7 @@ PF_OK, PF_ERR_NULL, PF_ERR_SHAPE, PF_ERR_UNSUPPORTED, PF_ERR_ALIGN, PF_ERR_WORKS
 PF_F32, PF_BF16 = 0, 1
 
 EXPORTS = ["pf_version", "pf_status_str", "pf_delta_fwd_supported", "pf_delta_fwd_block", "pf_delta_fwd_workspace_bytes",
-           "pf_delta_fwd", "pf_delta_product_fwd", "pf_flow_fwd_supported", "pf_flow_fwd", "pf_delta_chunk_flow", "pf_delta_chunk_scan",
+           "pf_delta_fwd", "pf_delta_product_fwd", "pf_beta_exponential", "pf_flow_fwd_supported", "pf_flow_fwd", "pf_delta_chunk_flow", "pf_delta_chunk_scan",
            "pf_delta_chunk_sigdelta_supported", "pf_delta_chunk_sigdelta_workspace_bytes", "pf_delta_chunk_sigdelta"]
 
 
@@ -44,6 +44,8 @@ def _load() -> ctypes.CDLL:
     lib.pf_delta_fwd.argtypes = [vp] * 7 + [i] * 8 + [vp, sz, vp]
     lib.pf_delta_product_fwd.restype = i
     lib.pf_delta_product_fwd.argtypes = [vp] * 7 + [i] * 8 + [vp, sz, vp]
+    lib.pf_beta_exponential.restype = i
+    lib.pf_beta_exponential.argtypes = [vp] * 3 + [i] * 6 + [vp]
     lib.pf_flow_fwd_supported.restype = i
     lib.pf_flow_fwd_supported.argtypes = [i, i, i, i, i]
     lib.pf_flow_fwd.restype = i
@@ -116,6 +118,11 @@ def pf_delta_product_fwd(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk,
     return int(_lib.pf_delta_product_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(beta), _ptr(S0), _ptr(O), _ptr(S_L),
                                          B, H, L, d_k, d_v, r, chunk, dt, _ptr(workspace), workspace_bytes,
                                          _stream_handle(stream)))
+
+
+def pf_beta_exponential(K, beta, beta_out, B, H, L, d_k, r, dt, stream=None) -> int:
+    return int(_lib.pf_beta_exponential(_ptr(K), _ptr(beta), _ptr(beta_out), B, H, L, d_k, r, dt,
+                                        _stream_handle(stream)))
 
 
 def pf_flow_fwd_supported(d_k, d_v, r, chunk, dt) -> int:

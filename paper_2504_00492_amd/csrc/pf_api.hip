@@ -275,6 +275,18 @@ pf_status pf_delta_chunk_scan(const void *Q, const void *K, const void *V, const
     return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
 }
 
+pf_status pf_beta_exponential(const void *K, const void *beta, void *beta_out, int B, int H, int L, int d_k,
+                              int r, pf_dtype dt, pf_stream stream)
+{
+    if (L != 0 && (!K || !beta || !beta_out)) return PF_ERR_NULL;
+    if (B <= 0 || H <= 0 || L < 0 || d_k <= 0 || r <= 0 || (long long)B * H > 0x7fffffffLL) return PF_ERR_SHAPE;
+    if (dt != PF_F32 && dt != PF_BF16) return PF_ERR_UNSUPPORTED;
+    if (!aligned16(K) || !aligned16(beta) || !aligned16(beta_out)) return PF_ERR_ALIGN;
+    hipError_t e = pf::launch_beta_exponential(K, beta, beta_out, (long long)B * H * L * r, d_k, dt == PF_BF16,
+                                               static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+}
+
 int pf_delta_chunk_sigdelta_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt)
 {
     if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return 0;

@@ -51,4 +51,8 @@ size_t sigdelta_workspace_bytes(int heads, int L, int r, int chunk);
 hipError_t launch_sigdelta(const void *K, const void *V, const void *beta, float *W, float *U, float *Gm,
                            int heads, int L, int dk, int dv, int r, int chunk, bool is_bf16, hipStream_t stream);
 
+// ---- exact rank-1 step size of Section 3.3 (pf_rescale.hip): one value per row of K
+hipError_t launch_beta_exponential(const void *K, const void *beta, void *beta_out, long long rows, int dk,
+                                   bool is_bf16, hipStream_t stream);
+
 }  // namespace pf

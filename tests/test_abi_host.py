@@ -215,3 +215,15 @@ def test_sigdelta_entry_checks(pf):
     assert call(K=p + 2) == pf.PF_ERR_ALIGN
     assert call(ws=p + 4) == pf.PF_ERR_ALIGN
     assert call(L=0, K=None, W=None, ws=None, wb=0) == pf.PF_OK
+
+
+def test_beta_exponential_checks(pf):
+    p = 1 << 20
+    f = pf.pf_beta_exponential
+    assert f(None, p, p, 1, 1, 8, 16, 1, pf.PF_F32, 0) == pf.PF_ERR_NULL
+    assert f(p, p, None, 1, 1, 8, 16, 1, pf.PF_F32, 0) == pf.PF_ERR_NULL
+    assert f(p, p, p, 0, 1, 8, 16, 1, pf.PF_F32, 0) == pf.PF_ERR_SHAPE
+    assert f(p, p, p, 1, 1, 8, 0, 1, pf.PF_F32, 0) == pf.PF_ERR_SHAPE
+    assert f(p, p, p, 1, 1, 8, 16, 1, 3, 0) == pf.PF_ERR_UNSUPPORTED
+    assert f(p + 2, p, p, 1, 1, 8, 16, 1, pf.PF_BF16, 0) == pf.PF_ERR_ALIGN
+    assert f(None, None, None, 1, 1, 0, 16, 1, pf.PF_BF16, 0) == pf.PF_OK     # empty sequence
