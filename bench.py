@@ -72,6 +72,7 @@ def main():
                     help="cfg0, cfg1, cfg2, cfg3a, cfg3b, cfg4 (see paper_2504_00492_amd/synth.py)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seq-len", type=int, default=0, help="override the workload's L (experiments only)")
+    ap.add_argument("--chunk", type=int, default=0, help="override the workload's chunk (experiments only)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="after the timed region, run a plain device-to-device copy of this many MiB "
                          "(a kernel of known traffic to scale rocprofv3 FETCH_SIZE / WRITE_SIZE by)")
@@ -94,6 +95,8 @@ def main():
     w = synth.WORKLOADS[args.workload]
     if args.seq_len > 0:
         w = w.with_(L=args.seq_len, name=f"{w.name}@L={args.seq_len}")
+    if args.chunk > 0:
+        w = w.with_(chunk=args.chunk, name=f"{w.name}@chunk={args.chunk}")
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
@@ -255,6 +258,9 @@ def main():
         "config": {"workload": f"{w.name}: B={B} H={H} L={L} d_k=d_v={dk} r={r} chunk={C} {w.dtype}",
                    "kernel_family": {1: "generic", 2: "mfma"}[fam], "flow_block": block},
         "alg_tflops": alg_tflops, "frac_bf16_mfma_peak": alg_tflops / PEAK_BF16_TFLOPS,
+        # the same time priced with the flop count of the requested chunk (what a run blocked at
+        # that chunk would have executed); equal to alg_tflops when flow_block == chunk
+        "alg_tflops_at_requested_chunk": flops_per_token_head(dk, r, C) * token_heads / (ms_per_step * 1e-3) / 1e12,
         "token_heads_per_s": token_heads / (ms_per_step * 1e-3),
         "min_hbm_gbs": min_bytes / (ms_per_step * 1e-3) / 1e9,
         "frac_hbm_peak_min_traffic": min_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,

@@ -65,7 +65,7 @@ const char *pf_status_str(pf_status s);
  *      any d_k, d_v, r, chunk whose per-chunk working set fits 160 KiB of LDS; both dtypes;
  *      L need not be a multiple of chunk (the tail is a shorter last chunk)
  *   2  MFMA path (PF_BF16 only): d_k = d_v in {64, 128} and a flow block (see
- *      pf_delta_fwd_block) with block * r in {64, 128, 256}, block in {64, 128}.  Any L: the
+ *      pf_delta_fwd_block) with block * r in {64, 128, 256}, block in {32, 64, 128}.  Any L: the
  *      L % block tokens left over at the end of every (b, h) are taken by the generic kernel
  *      from the state the whole blocks leave behind (the flows compose, Section 3.1).
  *      With few (b, h) pairs and a long L (the plain scan would use at most an eighth of the
@@ -77,12 +77,14 @@ const char *pf_status_str(pf_status s);
  */
 int pf_delta_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt);
 
-/* Tokens per flow block the MFMA path uses for these dimensions: chunk itself when chunk * r
- * virtual tokens fit a kernel instance (at most 256), else chunk / 2^j for the smallest j that
- * does.  The flow over a chunk is the composition of the flows over consecutive pieces of it
- * (Section 3.1), so O and S_L are the same function of the inputs either way; only the
- * blocking of the arithmetic, hence its rounding, differs.  0 when pf_delta_fwd_supported(...)
- * is not 2.  Host only. */
+/* Tokens per flow block the MFMA path uses for these dimensions: chunk / 2^j for the smallest j
+ * (j = 0 included) whose block has a kernel instance and at most 128 virtual tokens (block * r);
+ * failing that, for the smallest j whose block has an instance at all (256 virtual tokens).
+ * Smaller blocks are preferred because the per-block hand-over array grows with the square of the
+ * block.  The flow over a chunk is the composition of the flows over consecutive pieces of it
+ * (Section 3.1), so O and S_L are the same function of the inputs either way; only the blocking of
+ * the arithmetic, hence its rounding, differs.  0 when pf_delta_fwd_supported(...) is not 2.
+ * Host only. */
 int pf_delta_fwd_block(int d_k, int d_v, int r, int chunk, pf_dtype dt);
 
 /* Bytes of device scratch pf_delta_fwd needs for these dimensions (0 for the generic path, for
@@ -183,8 +185,9 @@ pf_status pf_flow_fwd(const void *Q, const void *A, const void *Atil, const void
 
 /*
  * Step 2 of Section 3 on its own ("parallel compute": the flow of every chunk, no dependence
- * between chunks), MFMA path only and only for chunk == pf_delta_fwd_block(...) (else
- * PF_ERR_UNSUPPORTED).  With n = chunk * r,
+ * between chunks), MFMA path only: d_k = d_v in {64, 128} and (chunk * r, chunk) one of (64, 64),
+ * (128, 32), (128, 64), (128, 128), (256, 64), (256, 128), else PF_ERR_UNSUPPORTED; L a multiple of
+ * chunk, else PF_ERR_SHAPE.  With n = chunk * r,
  * d = d_k = d_v and NC = L / chunk, for every (b, h, c):
  *
  *   Cmat = Id + M (.) diag(beta) K K^T,  M[(t,i),(s,j)] = 1 iff s < t     (Theorem 3.2 in delta

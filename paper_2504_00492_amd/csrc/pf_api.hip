@@ -63,17 +63,30 @@ int tail_chunk(int d, int r)
     return 0;
 }
 
-// Tokens per flow block on the MFMA path: the requested chunk, halved until chunk * r virtual
-// tokens fit a kernel instance (the flow over a chunk is the composition of the flows over
-// its halves, Section 3.1).  0 when no instance serves these dimensions.
+// Tokens per flow block on the MFMA path: the requested chunk or chunk / 2^j (the flow over a
+// chunk is the composition of the flows over its pieces, Section 3.1).  Blocks of at most 128
+// virtual tokens are preferred where an instance exists: the hand-over array T grows with the
+// square of the block, and every d_v tile of a head reads all of it (measured on 32 heads x 65536
+// tokens, r = 2: 2.45 ms with blocks of 64 tokens against 3.31 ms with blocks of 128).  Else the
+// largest block that has an instance.  0 when no instance serves these dimensions.
 int mfma_block(int d_k, int d_v, int r, int chunk, pf_dtype dt)
 {
     if (dt != PF_BF16 || d_k != d_v) return 0;
+    int any = 0;
     for (int c = chunk; c >= 16; c /= 2) {
-        if ((long long)c * r <= 4096 && pf::mfma_instance_exists(d_k, c * r, c)) return c;
+        if ((long long)c * r <= 4096 && pf::mfma_instance_exists(d_k, c * r, c)) {
+            if (c * r <= 128) return c;
+            if (!any) any = c;
+        }
         if (c % 2 != 0) break;
     }
-    return 0;
+    return any;
+}
+
+// The split entry points take any (d, chunk * r, chunk) that has an instance.
+bool split_instance(int d_k, int d_v, int r, int chunk)
+{
+    return d_k == d_v && (long long)chunk * r <= 4096 && pf::mfma_instance_exists(d_k, chunk * r, chunk);
 }
 
 int family(int d_k, int d_v, int r, int chunk, pf_dtype dt)
@@ -248,7 +261,7 @@ pf_status pf_delta_chunk_flow(const void *Q, const void *K, const void *beta, vo
     if (!Q || !K || !beta || !Tt || !Pt) return PF_ERR_NULL;
     pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
     if (st != PF_OK) return st;
-    if (mfma_block(d_k, d_v, r, chunk, PF_BF16) != chunk) return PF_ERR_UNSUPPORTED;
+    if (!split_instance(d_k, d_v, r, chunk)) return PF_ERR_UNSUPPORTED;
     if (L % chunk != 0) return PF_ERR_SHAPE;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(beta) || !aligned16(Tt) || !aligned16(Pt))
         return PF_ERR_ALIGN;
@@ -265,7 +278,7 @@ pf_status pf_delta_chunk_scan(const void *Q, const void *K, const void *V, const
     if (!Q || !K || !V || !beta || !Tt || !Pt || !O) return PF_ERR_NULL;
     pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
     if (st != PF_OK) return st;
-    if (mfma_block(d_k, d_v, r, chunk, PF_BF16) != chunk) return PF_ERR_UNSUPPORTED;
+    if (!split_instance(d_k, d_v, r, chunk)) return PF_ERR_UNSUPPORTED;
     if (L % chunk != 0) return PF_ERR_SHAPE;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(beta) || !aligned16(Tt) ||
         !aligned16(Pt) || !aligned16(S0) || !aligned16(O) || !aligned16(S_L))

@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     constexpr int CT = C / 16;         // 16-row tiles of tokens
     constexpr int MPW = D / 64;        // d_k tiles (16 rows of S^T) owned by one state wave
     constexpr int M1 = MT / 4;         // 16-row tiles of R / U_eff per state wave
-    constexpr int T2 = CT / 4;         // 16-token tiles of O per io wave
+    constexpr int T2 = (CT + 3) / 4;   // 16-token tiles of O per wave of a role (waves beyond CT own none)
     constexpr int KP = Ld::KP, VP = Ld::VP, SP = Ld::SP, UP = Ld::UP, OP = Ld::OP;
     constexpr int NTHR = kScanRoleThreads;
     constexpr bool kDoubleK = Ld::kDoubleK;
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     constexpr bool kStateReadout = RO && N <= 128;
     constexpr bool kIoReadout = RO && N > 128;
     static_assert(D % 64 == 0 && TV % 16 == 0 && N % 32 == 0, "tile shapes");
-    static_assert(MT % 4 == 0 && CT % 4 == 0, "every wave of a role owns the same number of tiles");
+    static_assert(MT % 4 == 0 && (CT % 4 == 0 || CT < 4), "tiles are dealt evenly, or at most one token tile per wave");
     static_assert(N <= NTHR, "beta of a chunk is fetched by one pass");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -161,7 +161,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         // readout by the state waves (kStateReadout): token tiles of O owned by this wave, W and
         // (with 8 tiles) 7 - W; token tile tt sees virtual tokens < R (16 tt + 16)
         constexpr auto tok_tile = [](int i) constexpr { return CT >= 8 ? ((i & 1) ? 8 * (i >> 1) + 7 - W : 8 * (i >> 1) + W) : W + 4 * i; };
-        constexpr auto ksteps_of = [](int tt) constexpr { return (R * (16 * tt + 16) + 31) / 32; };
+        // (a chunk of fewer than 64 tokens has fewer tiles than waves: the waves beyond own none)
+        constexpr auto ksteps_of = [](int tt) constexpr { return tt < CT ? (R * (16 * tt + 16) + 31) / 32 : 0; };
         bf16x8 p2[T2][NKT];        // P tiles of this wave's token tiles (those the causal mask keeps)
         auto fetch_p = [&](size_t cid) {
             const bf16 *Pc = Pt + cid * (size_t)C * N;
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             for (int i = 0; i < T2; ++i)
 #pragma unroll
                 for (int ks = 0; ks < NKS; ++ks)
-                    bQ[i][ks] = ld8(Qc + (size_t)(16 * tok_tile(i) + r16) * D + 32 * ks + 8 * g);
+                    if (tok_tile(i) < CT) bQ[i][ks] = ld8(Qc + (size_t)(16 * tok_tile(i) + r16) * D + 32 * ks + 8 * g);
         };
 
         bf16x8 t1[M1][NKT];        // T tiles of this wave's rows of U_eff (those below the diagonal)
@@ -266,6 +267,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                     // operand of K S^T are, lane for lane, the A operand here
 #pragma unroll
                     for (int i = 0; i < T2; ++i) {
+                        if (tok_tile(i) >= CT) continue;
 #pragma unroll
                         for (int md = 0; md < NNT; ++md) oacc[i][md] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -366,7 +368,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 for (int i = 0; i < T2; ++i)
 #pragma unroll
                     for (int md = 0; md < NNT; ++md)
-                        st4(&Ob[(16 * tok_tile(i) + r16) * OP + 16 * md + 4 * g], cvt4(oacc[i][md]));
+                        if (tok_tile(i) < CT) st4(&Ob[(16 * tok_tile(i) + r16) * OP + 16 * md + 4 * g], cvt4(oacc[i][md]));
                 fetch_p(nx);
             }
             if (!kDoubleK) __syncthreads();   // interval 3: the io waves overwrite K in place
@@ -401,7 +403,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         // token tiles of O owned by this wave: W and (with 8 tiles) 7 - W
         constexpr auto tok_tile = [](int i) constexpr { return CT >= 8 ? ((i & 1) ? 8 * (i >> 1) + 7 - W : 8 * (i >> 1) + W) : W + 4 * i; };
         // causal readout: token tile tt sees virtual tokens < R (16 tt + 16)
-        constexpr auto ksteps_of = [](int tt) constexpr { return (R * (16 * tt + 16) + 31) / 32; };
+        constexpr auto ksteps_of = [](int tt) constexpr { return tt < CT ? (R * (16 * tt + 16) + 31) / 32 : 0; };
 
         // K moves in two halves (vectors [0, KH) and [KH, KV) of every thread) so that its
         // staging and load issue can be spread over two intervals
@@ -442,7 +444,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             for (int i = 0; i < T2; ++i)
 #pragma unroll
                 for (int ks = 0; ks < NKS; ++ks)
-                    bQ[i][ks] = ld8(Qc + (size_t)(16 * tok_tile(i) + r16) * D + 32 * ks + 8 * g);
+                    if (tok_tile(i) < CT) bQ[i][ks] = ld8(Qc + (size_t)(16 * tok_tile(i) + r16) * D + 32 * ks + 8 * g);
         };
         auto stage_k = [&](bf16 *Kd, int q0, int q1) {
 #pragma unroll
@@ -508,6 +510,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 LDS_FENCE();
 #pragma unroll
                 for (int i = 0; i < T2; ++i) {
+                    if (tok_tile(i) >= CT) continue;
 #pragma unroll
                     for (int md = 0; md < NNT; ++md) oacc[i][md] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -534,7 +537,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             if constexpr (kIoReadout) {
                 constexpr int KMAX = ksteps_of(tok_tile(T2 - 1)) > ksteps_of(tok_tile(0)) ? ksteps_of(tok_tile(T2 - 1))
                                                                                           : ksteps_of(tok_tile(0));
-                constexpr int KM = KMAX < NKT ? KMAX : NKT;
+                constexpr int KM = KMAX < 1 ? 1 : (KMAX < NKT ? KMAX : NKT);
                 bf16x8 aU[KM][NNT];
 #pragma unroll
                 for (int kt = 0; kt < KM; ++kt)
@@ -545,6 +548,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 #pragma unroll
                 for (int i = 0; i < T2; ++i) {
                     const int tt = tok_tile(i);
+                    if (tt >= CT) continue;
 #pragma unroll
                     for (int kt = 0; kt < KM; ++kt)
                         if (kt < ksteps_of(tt)) {
@@ -585,8 +589,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 
 // ---------------------------------------------------------------------------- host side
 #define PF_SCAN_INSTANCES(X) \
-    X(64, 64, 64) X(64, 128, 64) X(64, 128, 128) X(64, 256, 64) X(64, 256, 128) \
-    X(128, 64, 64) X(128, 128, 64) X(128, 128, 128) X(128, 256, 64) X(128, 256, 128)
+    X(64, 64, 64) X(64, 128, 32) X(64, 128, 64) X(64, 128, 128) X(64, 256, 64) X(64, 256, 128) \
+    X(128, 64, 64) X(128, 128, 32) X(128, 128, 64) X(128, 128, 128) X(128, 256, 64) X(128, 256, 128)
 
 template <int D, int N, int C, int TV, bool RO>
 static hipError_t launch_scan_ro(const void *Q, const void *K, const void *V, const void *beta,

@@ -44,17 +44,24 @@ def test_version_and_status_strings(pf):
 def test_flow_block(pf):
     F32, BF = pf.PF_F32, pf.PF_BF16
     assert pf.pf_delta_fwd_block(128, 128, 2, 64, BF) == 64
-    assert pf.pf_delta_fwd_block(128, 128, 2, 128, BF) == 128
-    assert pf.pf_delta_fwd_block(128, 128, 4, 128, BF) == 64            # 512 virtual tokens -> 2 x 256
+    assert pf.pf_delta_fwd_block(128, 128, 2, 128, BF) == 64            # 256 virtual tokens -> 2 x 128
+    assert pf.pf_delta_fwd_block(128, 128, 4, 128, BF) == 32            # 512 virtual tokens -> 4 x 128
+    assert pf.pf_delta_fwd_block(128, 128, 4, 64, BF) == 32
+    assert pf.pf_delta_fwd_block(128, 128, 1, 128, BF) == 128           # 128 virtual tokens as they are
+    assert pf.pf_delta_fwd_block(128, 128, 8, 64, BF) == 0
+    assert pf.pf_delta_fwd_block(128, 128, 8, 32, BF) == 0              # (256, 32) has no instance, 16 x 8 neither
     assert pf.pf_delta_fwd_block(64, 64, 1, 512, BF) == 128
     assert pf.pf_delta_fwd_block(16, 16, 1, 16, F32) == 0
     assert pf.pf_delta_fwd_block(128, 128, 8, 64, BF) == 0
     # workspace follows the block, not the requested chunk
     assert (pf.pf_delta_fwd_workspace_bytes(2, 16, 8192, 128, 128, 4, 128, BF)
             == pf.pf_delta_fwd_workspace_bytes(2, 16, 8192, 128, 128, 4, 64, BF))
-    # the split entry points only take the block itself
+    # the split entry points take every (chunk * r, chunk) that has an instance, and nothing else
     fake = 0x1000
     assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 256, 128, 128, 4, 128, 0) == pf.PF_ERR_UNSUPPORTED
+    assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 256, 128, 128, 2, 32, 0) == pf.PF_ERR_UNSUPPORTED
+    assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 100, 128, 128, 4, 32, 0) == pf.PF_ERR_SHAPE
+    assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 100, 128, 128, 2, 128, 0) == pf.PF_ERR_SHAPE
 
 
 def test_supported_families(pf):

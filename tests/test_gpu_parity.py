@@ -78,7 +78,8 @@ def test_empty_sequence_returns_initial_state(pf):
 
 
 # ------------------------------------------------------------------ chunk flow (Theorem 3.2) on its own
-@pytest.mark.parametrize("d,r,C", [(64, 1, 64), (128, 2, 64), (128, 4, 64), (128, 2, 128), (128, 1, 128), (64, 4, 64)])
+@pytest.mark.parametrize("d,r,C", [(64, 1, 64), (128, 2, 64), (128, 4, 64), (128, 2, 128), (128, 1, 128), (64, 4, 64),
+                                   (128, 4, 32), (64, 4, 32)])
 def test_chunk_flow_matches_theorem(pf, oracle, d, r, C):
     """T and P of every chunk (decoded from their tiled layouts) against the numpy statement of
     Theorem 3.2: T is the inverse of the system matrix, T (beta K) = W and T (beta V) = -U; then the
@@ -263,11 +264,11 @@ def test_more_workgroups_than_the_gpu_holds(pf, oracle):
 
 
 def test_chunk_beyond_one_flow_block(pf, oracle):
-    """r = 4, chunk = 128 is 512 virtual tokens: it runs as flow blocks of 64 tokens
+    """r = 4, chunk = 128 is 512 virtual tokens: it runs as flow blocks of 32 tokens
     (pf_delta_fwd_block), against the oracle and bit-identical to chunk = 64."""
     import torch
     w = synth.WORKLOADS["cfg3b"].with_(B=1, H=3, L=512)
-    assert pf.pf_delta_fwd_block(w.d_k, w.d_v, w.r, w.chunk, pf.PF_BF16) == 64
+    assert pf.pf_delta_fwd_block(w.d_k, w.d_v, w.r, w.chunk, pf.PF_BF16) == 32
     _check(pf, oracle, w, expect_family=2)
     inp = synth.make_inputs(w)
     dev = to_device(w, inp)
@@ -279,9 +280,10 @@ def test_chunk_beyond_one_flow_block(pf, oracle):
 
 @pytest.mark.parametrize("name,kw", [
     ("cfg2", dict(B=1, H=3, L=3 * 64 + 37)),          # whole blocks + a tail of 37 tokens
-    ("cfg3b", dict(B=1, H=2, L=2 * 64 + 5)),          # chunk 128 -> blocks of 64, tail 5, S0 != 0
+    ("cfg3b", dict(B=1, H=2, L=2 * 64 + 5)),          # chunk 128 -> blocks of 32, tail 5, S0 != 0
     ("cfg1", dict(B=2, H=2, L=64 + 63)),              # d = 64, tail one token short of a block
-    ("cfg4", dict(B=1, H=2, L=100)),                  # shorter than one block (128): all of it is tail
+    ("cfg4", dict(B=1, H=2, L=100)),                  # chunk 128 -> one block of 64 and a tail of 36
+    ("cfg4", dict(B=1, H=2, L=50)),                   # shorter than one block: all of it is tail
 ])
 def test_mfma_path_ragged_length(pf, oracle, name, kw):
     """L need not be a multiple of the flow block: the tail of every head runs on the generic
@@ -356,8 +358,9 @@ def test_segment_parallel_scan(pf, oracle, name, kw):
     w = synth.WORKLOADS[name].with_(**kw)
     B, H, L, r, d = w.B, w.H, w.L, w.r, w.d_k
     # the segment buffers show in the workspace size: more than T and P alone
-    n = w.chunk * r
-    plain = B * H * (L // w.chunk) * (n * n + w.chunk * n) * 2
+    blk = pf.pf_delta_fwd_block(d, d, r, w.chunk, pf.PF_BF16)
+    n = blk * r
+    plain = B * H * (L // blk) * (n * n + blk * n) * 2
     need = pf.pf_delta_fwd_workspace_bytes(B, H, L, d, d, r, w.chunk, pf.PF_BF16)
     assert need > plain + 3 * B * H * 4 * d * d * 4
     _check(pf, oracle, w, expect_family=2)
