@@ -205,8 +205,9 @@ def main():
                     "unit": "TFLOP/s", "frac": tfl / PEAK_F32_VALU_TFLOPS, "avg_kernel_ms": ms_per_step,
                     "traffic": None}
     solvers = None
-    if args.compare_solvers and pf.pf_delta_chunk_sigdelta_supported(dk, dv, r, C, dt):
-        sneed = pf.pf_delta_chunk_sigdelta_workspace_bytes(B, H, L, r, C)
+    if args.compare_solvers and pf.pf_delta_chunk_sigdelta_supported(dk, dv, r, block, dt):
+        Cs = block                       # both solvers on the same blocks
+        sneed = pf.pf_delta_chunk_sigdelta_workspace_bytes(B, H, L, r, Cs)
         sws = torch.empty(sneed, dtype=torch.uint8, device=dev)
         Wo = torch.empty((B, H, L, r, dk), dtype=torch.float32, device=dev)
         Uo = torch.empty((B, H, L, r, dv), dtype=torch.float32, device=dev)
@@ -215,18 +216,18 @@ def main():
         for i in range(1 + nrep):
             if i >= 1:
                 evs[i - 1][0].record(stream)
-            st = pf.pf_delta_chunk_sigdelta(K, V, beta, Wo, Uo, B, H, L, dk, dv, r, C, dt, sws, sneed, stream)
+            st = pf.pf_delta_chunk_sigdelta(K, V, beta, Wo, Uo, B, H, L, dk, dv, r, Cs, dt, sws, sneed, stream)
             assert st == pf.PF_OK, st
             if i >= 1:
                 evs[i - 1][1].record(stream)
         torch.cuda.synchronize()
         t_sig = sum(a.elapsed_time(b) for a, b in evs) / nrep
-        n_sig = C * r
+        n_sig = Cs * r
         # useful fp32 operations of the sweep: C(C-1)/2 grid cells, r rows of d_k + d_v columns, 2 + r
         # additions / multiply-adds each (counted as 2 flops), per chunk-head
-        sig_flops = (C * (C - 1) // 2) * r * (dk + dv) * (2 + r) * 2 * (token_heads / C)
+        sig_flops = (Cs * (Cs - 1) // 2) * r * (dk + dv) * (2 + r) * 2 * (token_heads / Cs)
         solvers = {
-            "sigdelta": {"ms": t_sig, "chunk": C, "n": n_sig, "gives": "W, U fp32 (Gram kernel + sweep kernel)",
+            "sigdelta": {"ms": t_sig, "chunk": Cs, "n": n_sig, "gives": "W, U fp32 (Gram kernel + sweep kernel)",
                          "sweep_tflops_fp32": sig_flops / (t_sig * 1e-3) / 1e12,
                          "frac_fp32_valu_peak": sig_flops / (t_sig * 1e-3) / 1e12 / PEAK_F32_VALU_TFLOPS},
             "block_substitution": {"ms": kernels.get("flow_kernel", {}).get("ms"), "chunk": block, "n": block * r,
