@@ -66,8 +66,11 @@ def kernel_bytes_per_token_head(d, r, e):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    # Defaults long enough for the clocks to settle: on this GPU the first few milliseconds of a
+    # burst of launches run up to 20 % slower than the steady state (20 steps after 5: 0.277 ms per
+    # step on config 2; 400 after 100: 0.23 ms).
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="cfg2",
                     help="cfg0, cfg1, cfg2, cfg3a, cfg3b, cfg4 (see paper_2504_00492_amd/synth.py)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -211,7 +214,7 @@ def main():
         sws = torch.empty(sneed, dtype=torch.uint8, device=dev)
         Wo = torch.empty((B, H, L, r, dk), dtype=torch.float32, device=dev)
         Uo = torch.empty((B, H, L, r, dv), dtype=torch.float32, device=dev)
-        nrep = max(3, args.steps // 4)
+        nrep = min(10, max(3, args.steps // 4))
         evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(nrep)]
         for i in range(1 + nrep):
             if i >= 1:
