@@ -29,6 +29,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 PEAK_F32_VALU_TFLOPS = 157.3   # MI355X fp32 vector, published
+SETTLE_S = 0.15                # untimed busy time before any timed region (clock settling)
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 
 
@@ -148,6 +149,16 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    # Whatever W is, keep warming up (untimed) until the GPU has been busy for SETTLE_S seconds:
+    # the clocks need that long to settle (see the defaults above), and a short W would time the
+    # transient instead of the throughput of the job.
+    settle_steps = 0
+    ts = time.perf_counter()
+    while time.perf_counter() - ts < SETTLE_S and settle_steps < 20000:
+        for i in range(20):
+            step(args.warmup + settle_steps + i)
+        settle_steps += 20
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i)
@@ -176,8 +187,9 @@ def main():
         mk = lambda m: torch.empty((B, H, NC, m), dtype=torch.bfloat16, device=dev)
         Tt, Pt = mk(n * n), mk(block * n)
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-        for i in range(args.warmup + args.steps):
-            j = i - args.warmup
+        nwarm = args.warmup + settle_steps
+        for i in range(nwarm + args.steps):
+            j = i - nwarm
             if j >= 0:
                 ev[j][0].record(stream)
             st = pf.pf_delta_chunk_flow(Q, K, beta, Tt, Pt, B, H, L, dk, dv, r, block, stream)
@@ -257,6 +269,7 @@ def main():
     out = {
         "metric": "tokens/s, chunked rank-r DeltaNet fwd, 1 MI355X",
         "value": tok_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "settle_steps": settle_steps,   # further untimed steps after the W warm-up steps (>= 0.15 s of GPU work)
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: B={B} H={H} L={L} d_k=d_v={dk} r={r} chunk={C} {w.dtype}",
