@@ -228,14 +228,14 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 bf16x8 bS[NNT][NKS], aK[M1][NKS];
                 bf16x4 vt[M1][NNT];
                 f32x4 bt[M1];
+                // reads in the order the MFMAs below consume them, so that the first products can
+                // start while the later operands are still on their way
 #pragma unroll
-                for (int nt = 0; nt < NNT; ++nt)
+                for (int ks = 0; ks < NKS; ++ks) {
+                    aK[0][ks] = ld8(&Kc[(16 * W + r16) * KP + 32 * ks + 8 * g]);
 #pragma unroll
-                    for (int ks = 0; ks < NKS; ++ks) bS[nt][ks] = ld8(&Sb[(16 * nt + r16) * SP + 32 * ks + 8 * g]);
-#pragma unroll
-                for (int i = 0; i < M1; ++i)
-#pragma unroll
-                    for (int ks = 0; ks < NKS; ++ks) aK[i][ks] = ld8(&Kc[(16 * (W + 4 * i) + r16) * KP + 32 * ks + 8 * g]);
+                    for (int nt = 0; nt < NNT; ++nt) bS[nt][ks] = ld8(&Sb[(16 * nt + r16) * SP + 32 * ks + 8 * g]);
+                }
 #pragma unroll
                 for (int i = 0; i < M1; ++i) {
                     const int mt = W + 4 * i;
@@ -244,6 +244,11 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 #pragma unroll
                     for (int nt = 0; nt < NNT; ++nt)
                         vt[i][nt] = lds_read_tr4(&Vs[(16 * mt + 4 * g + (r16 >> 2)) * VP + 16 * nt + 4 * (r16 & 3)]);
+                    if (i + 1 < M1) {
+#pragma unroll
+                        for (int ks = 0; ks < NKS; ++ks)
+                            aK[i + 1][ks] = ld8(&Kc[(16 * (W + 4 * (i + 1)) + r16) * KP + 32 * ks + 8 * g]);
+                    }
                 }
                 LDS_FENCE();
 #pragma unroll
