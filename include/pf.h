@@ -61,9 +61,10 @@ const char *pf_status_str(pf_status s);
 
 /* Which kernel family would serve these dimensions.  Host only, no GPU needed.
  *   0  unsupported (pf_delta_fwd would return PF_ERR_UNSUPPORTED)
- *   1  generic path: one workgroup per (b, h), fp32 vector arithmetic, chunk state in LDS;
- *      any d_k, d_v, r, chunk whose per-chunk working set fits 160 KiB of LDS; both dtypes;
- *      L need not be a multiple of chunk (the tail is a shorter last chunk)
+ *   1  generic path: one workgroup per (b, h), fp32 vector arithmetic, chunk state in LDS; both
+ *      dtypes, any d_k, d_v, r; the chunk is halved until its working set fits 160 KiB of LDS next
+ *      to the fp32 state (unsupported only when not even one token does); L need not be a
+ *      multiple of chunk (the tail is a shorter last chunk)
  *   2  MFMA path (PF_BF16 only): d_k = d_v in {64, 128} and a flow block (see
  *      pf_delta_fwd_block) with block * r in {64, 128, 256}, block in {32, 64, 128}.  Any L: the
  *      L % block tokens left over at the end of every (b, h) are taken by the generic kernel
@@ -77,14 +78,14 @@ const char *pf_status_str(pf_status s);
  */
 int pf_delta_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt);
 
-/* Tokens per flow block the MFMA path uses for these dimensions: chunk / 2^j for the smallest j
+/* Tokens per flow block actually used for these dimensions.  MFMA path: chunk / 2^j for the smallest j
  * (j = 0 included) whose block has a kernel instance and at most 128 virtual tokens (block * r);
  * failing that, for the smallest j whose block has an instance at all (256 virtual tokens).
  * Smaller blocks are preferred because the per-block hand-over array grows with the square of the
  * block.  The flow over a chunk is the composition of the flows over consecutive pieces of it
  * (Section 3.1), so O and S_L are the same function of the inputs either way; only the blocking of
- * the arithmetic, hence its rounding, differs.  0 when pf_delta_fwd_supported(...) is not 2.
- * Host only. */
+ * the arithmetic, hence its rounding, differs.  On the generic path: the requested chunk, halved
+ * until its working set fits LDS.  0 when pf_delta_fwd_supported(...) is 0.  Host only. */
 int pf_delta_fwd_block(int d_k, int d_v, int r, int chunk, pf_dtype dt);
 
 /* Bytes of device scratch pf_delta_fwd needs for these dimensions (0 for the generic path, for
@@ -173,7 +174,8 @@ pf_status pf_beta_exponential(const void *K, const void *beta, void *beta_out,
  *   S0, O, S_L, stream               as for pf_delta_fwd
  *
  * The delta rule is the special case A = beta k, Atil = -beta v, B = -k.  Served by the generic
- * kernel family only (pf_flow_fwd_supported tells whether the chunk's working set fits LDS);
+ * kernel family only (pf_flow_fwd_supported: 1 unless not even one token's working set fits LDS;
+ * the chunk is halved until it fits, as for pf_delta_fwd);
  * needs no workspace; L need not be a multiple of chunk; L == 0 is valid as for pf_delta_fwd.
  * Same error behaviour as pf_delta_fwd.
  */

@@ -89,14 +89,25 @@ bool split_instance(int d_k, int d_v, int r, int chunk)
     return d_k == d_v && (long long)chunk * r <= 4096 && pf::mfma_instance_exists(d_k, chunk * r, chunk);
 }
 
+// Tokens per chunk on the generic path: the requested chunk when its working set fits LDS next
+// to the fp32 state, else the chunk halved until it does (the flow over a chunk is the composition
+// of the flows over its pieces; the generic kernel takes a shorter last piece anyway).  0 when
+// not even one token fits (the state alone is too large).
+int generic_block(int d_k, int d_v, int r, int chunk)
+{
+    if (d_k > 65536 || d_v > 65536 || r > 65536) return 0;
+    int c = chunk > 65536 / r ? 65536 / r : chunk;
+    if (c < 1) return 0;
+    while (c > 1 && pf::generic_lds_bytes(d_k, d_v, r, c) > pf::kMaxLdsBytes) c = (c + 1) / 2;
+    return pf::generic_lds_bytes(d_k, d_v, r, c) <= pf::kMaxLdsBytes ? c : 0;
+}
+
 int family(int d_k, int d_v, int r, int chunk, pf_dtype dt)
 {
     if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return 0;
     if (dt != PF_F32 && dt != PF_BF16) return 0;
     if (mfma_block(d_k, d_v, r, chunk, dt) > 0) return 2;
-    if ((long long)chunk * r > 65536 || d_k > 65536 || d_v > 65536) return 0;
-    if (pf::generic_lds_bytes(d_k, d_v, r, chunk) <= pf::kMaxLdsBytes) return 1;
-    return 0;
+    return generic_block(d_k, d_v, r, chunk) > 0 ? 1 : 0;
 }
 
 pf_status check_dims(int B, int H, int L, int d_k, int d_v, int r, int chunk)
@@ -133,8 +144,9 @@ int pf_delta_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt)
 
 int pf_delta_fwd_block(int d_k, int d_v, int r, int chunk, pf_dtype dt)
 {
-    if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return 0;
-    return mfma_block(d_k, d_v, r, chunk, dt);
+    const int fam = family(d_k, d_v, r, chunk, dt);
+    if (fam == 2) return mfma_block(d_k, d_v, r, chunk, dt);
+    return fam == 1 ? generic_block(d_k, d_v, r, chunk) : 0;
 }
 
 size_t pf_delta_fwd_workspace_bytes(int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt)
@@ -159,7 +171,7 @@ static pf_status delta_fwd_impl(const void *Q, const void *K, const void *V, con
     if (fam == 0) return PF_ERR_UNSUPPORTED;
     // The MFMA kernels take whole flow blocks; the L % block tokens left over at the end of
     // every head go through the generic kernel, from the state the blocks leave behind.
-    const int block = fam == 2 ? mfma_block(d_k, d_v, r, chunk, dt) : chunk;
+    const int block = fam == 2 ? mfma_block(d_k, d_v, r, chunk, dt) : generic_block(d_k, d_v, r, chunk);
     const int tail = fam == 2 ? L % block : 0;
     const int tchunk = tail ? tail_chunk(d_k, r) : 0;
     if (tail && tchunk == 0) return PF_ERR_SHAPE;
@@ -171,7 +183,7 @@ static pf_status delta_fwd_impl(const void *Q, const void *K, const void *V, con
     if (fam == 1 || L < block) {
         // generic family, an empty sequence, or a sequence shorter than one flow block
         hipError_t e = pf::launch_generic(Q, K, V, beta, S0, O, S_L, heads, L, d_k, d_v, r,
-                                          fam == 1 ? chunk : (tchunk ? tchunk : 1), dt == PF_BF16, s, 0, product);
+                                          fam == 1 ? block : (tchunk ? tchunk : 1), dt == PF_BF16, s, 0, product);
         return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
     }
     const WorkspacePlan wp = plan_workspace(heads, L, d_k, r, block);
@@ -235,8 +247,7 @@ int pf_flow_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt)
 {
     if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return 0;
     if (dt != PF_F32 && dt != PF_BF16) return 0;
-    if ((long long)chunk * r > 65536 || d_k > 65536 || d_v > 65536) return 0;
-    return pf::generic_lds_bytes(d_k, d_v, r, chunk) <= pf::kMaxLdsBytes ? 1 : 0;
+    return generic_block(d_k, d_v, r, chunk) > 0 ? 1 : 0;
 }
 
 pf_status pf_flow_fwd(const void *Q, const void *A, const void *Atil, const void *Bm, const float *S0,
@@ -250,8 +261,9 @@ pf_status pf_flow_fwd(const void *Q, const void *A, const void *Atil, const void
     if (!aligned16(Q) || !aligned16(A) || !aligned16(Atil) || !aligned16(Bm) || !aligned16(O) ||
         !aligned16(S0) || !aligned16(S_L))
         return PF_ERR_ALIGN;
-    hipError_t e = pf::launch_generic_drivers(Q, A, Atil, Bm, S0, O, S_L, B * H, L, d_k, d_v, r, chunk,
-                                              dt == PF_BF16, static_cast<hipStream_t>(stream));
+    hipError_t e = pf::launch_generic_drivers(Q, A, Atil, Bm, S0, O, S_L, B * H, L, d_k, d_v, r,
+                                              generic_block(d_k, d_v, r, chunk), dt == PF_BF16,
+                                              static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
 }
 

@@ -48,11 +48,10 @@ def test_flow_block(pf):
     assert pf.pf_delta_fwd_block(128, 128, 4, 128, BF) == 32            # 512 virtual tokens -> 4 x 128
     assert pf.pf_delta_fwd_block(128, 128, 4, 64, BF) == 32
     assert pf.pf_delta_fwd_block(128, 128, 1, 128, BF) == 128           # 128 virtual tokens as they are
-    assert pf.pf_delta_fwd_block(128, 128, 8, 64, BF) == 0
-    assert pf.pf_delta_fwd_block(128, 128, 8, 32, BF) == 0              # (256, 32) has no instance, 16 x 8 neither
+    assert pf.pf_delta_fwd_block(128, 128, 8, 64, BF) == 4              # no MFMA instance for r = 8: generic path, 4 tokens
+    assert pf.pf_delta_fwd_block(128, 128, 8, 32, BF) == 4              # (256, 32) has no instance, 16 x 8 neither
     assert pf.pf_delta_fwd_block(64, 64, 1, 512, BF) == 128
-    assert pf.pf_delta_fwd_block(16, 16, 1, 16, F32) == 0
-    assert pf.pf_delta_fwd_block(128, 128, 8, 64, BF) == 0
+    assert pf.pf_delta_fwd_block(16, 16, 1, 16, F32) == 16             # generic path: the chunk itself
     # workspace follows the block, not the requested chunk
     assert (pf.pf_delta_fwd_workspace_bytes(2, 16, 8192, 128, 128, 4, 128, BF)
             == pf.pf_delta_fwd_workspace_bytes(2, 16, 8192, 128, 128, 4, 64, BF))
@@ -72,8 +71,11 @@ def test_supported_families(pf):
     assert pf.pf_delta_fwd_supported(128, 128, 4, 64, BF) == 2         # config 3, chunk 64
     assert pf.pf_delta_fwd_supported(128, 128, 2, 128, BF) == 2        # config 4
     assert pf.pf_delta_fwd_supported(128, 128, 4, 128, BF) == 2        # config 3, chunk 128: two blocks of 64
-    assert pf.pf_delta_fwd_supported(128, 128, 8, 64, BF) == 0         # 512 virtual tokens, no smaller block
-    assert pf.pf_delta_fwd_supported(128, 128, 2, 64, F32) == 0        # fp32 at that size: no LDS room
+    assert pf.pf_delta_fwd_supported(128, 128, 8, 64, BF) == 1         # r = 8: no MFMA instance, generic path
+    assert pf.pf_delta_fwd_supported(128, 128, 2, 64, F32) == 1        # fp32 at that size: generic path on smaller chunks
+    assert pf.pf_delta_fwd_block(128, 128, 2, 64, F32) == 16
+    assert pf.pf_delta_fwd_block(16, 16, 1, 16, F32) == 16             # fits as requested
+    assert pf.pf_delta_fwd_supported(256, 256, 1, 8, F32) == 0         # the fp32 state alone exceeds LDS
     assert pf.pf_delta_fwd_supported(20, 12, 3, 8, BF) == 1            # odd shape -> generic
     assert pf.pf_delta_fwd_supported(0, 16, 1, 16, F32) == 0
     assert pf.pf_delta_fwd_supported(16, 16, 1, 16, 7) == 0
@@ -133,7 +135,7 @@ def test_argument_checks_return_before_launch(pf):
     assert call(r=0) == pf.PF_ERR_SHAPE
     assert call(chunk=0) == pf.PF_ERR_SHAPE
     assert call(dt=5) == pf.PF_ERR_UNSUPPORTED
-    assert call(dt=pf.PF_F32) == pf.PF_ERR_UNSUPPORTED  # fp32 with d = 128, n = 128 does not fit LDS
+    assert call(dt=pf.PF_F32, d_k=256, d_v=256) == pf.PF_ERR_UNSUPPORTED  # fp32 state of 256 x 256 does not fit LDS
     assert call(Q=A + 2) == pf.PF_ERR_ALIGN
     assert call(SL=A + 4) == pf.PF_ERR_ALIGN
     assert call(ws=None) == pf.PF_ERR_WORKSPACE
@@ -157,7 +159,8 @@ def test_general_driver_entry_checks(pf):
     F32, BF = pf.PF_F32, pf.PF_BF16
     assert pf.pf_flow_fwd_supported(16, 16, 1, 16, F32) == 1
     assert pf.pf_flow_fwd_supported(20, 12, 3, 8, BF) == 1
-    assert pf.pf_flow_fwd_supported(128, 128, 2, 64, BF) == 0          # working set beyond 160 KiB of LDS
+    assert pf.pf_flow_fwd_supported(128, 128, 2, 64, BF) == 1          # runs on chunks of 16 tokens
+    assert pf.pf_flow_fwd_supported(300, 300, 1, 8, BF) == 0           # the fp32 state alone exceeds LDS
     assert pf.pf_flow_fwd_supported(16, 16, 1, 16, 9) == 0
     call = lambda Q=A, Ad=A, At=A, Bm=A, S0=A, O=A, SL=A, L=40, dk=16, dv=12, r=2, C=8, dt=F32: \
         pf.pf_flow_fwd(Q, Ad, At, Bm, S0, O, SL, 1, 2, L, dk, dv, r, C, dt, 0)
@@ -168,7 +171,7 @@ def test_general_driver_entry_checks(pf):
     assert call(O=None) == pf.PF_ERR_NULL
     assert call(L=-3) == pf.PF_ERR_SHAPE
     assert call(r=0) == pf.PF_ERR_SHAPE
-    assert call(dk=128, dv=128, C=64) == pf.PF_ERR_UNSUPPORTED
+    assert call(dk=300, dv=300, C=64) == pf.PF_ERR_UNSUPPORTED
     assert call(dt=4) == pf.PF_ERR_UNSUPPORTED
     assert call(Bm=A + 6) == pf.PF_ERR_ALIGN
     assert call(S0=A + 4) == pf.PF_ERR_ALIGN

@@ -62,6 +62,19 @@ def test_generic_fp32_shapes(pf, oracle, kw):
     _check(pf, oracle, w, expect_family=1)
 
 
+@pytest.mark.parametrize("dtype,kw", [
+    ("f32", dict(B=1, H=2, L=100, d_k=128, d_v=128, r=2, chunk=64, s0_std=0.2)),   # fp32 at d = 128: chunks of 16 tokens
+    ("bf16", dict(B=1, H=2, L=70, d_k=128, d_v=128, r=8, chunk=64)),               # r = 8 has no MFMA instance: chunks of 4
+    ("f32", dict(B=1, H=1, L=33, d_k=160, d_v=96, r=1, chunk=128, s0_std=0.1)),    # a state of 96 x 160 leaves room for 32 tokens
+])
+def test_generic_path_on_smaller_chunks(pf, oracle, dtype, kw):
+    """A chunk whose working set does not fit LDS is run as smaller chunks (the flows compose)."""
+    w = synth.Workload("gensmall", dtype, seed=13, **{"s0_std": 0.0, "reflect_frac": 0.0, **kw})
+    blk = pf.pf_delta_fwd_block(w.d_k, w.d_v, w.r, w.chunk, pf.PF_BF16 if dtype == "bf16" else pf.PF_F32)
+    assert 0 < blk < w.chunk
+    _check(pf, oracle, w, expect_family=1)
+
+
 def test_generic_bf16_odd_shape(pf, oracle):
     w = synth.Workload("gen16", "bf16", 2, 2, 48, 24, 40, 2, 8, seed=12, s0_std=0.2)
     _check(pf, oracle, w, expect_family=1)
