@@ -101,6 +101,9 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     constexpr bool kDoubleK = Ld::kDoubleK;
     // Who computes O: the state waves when their register budget allows (they already hold S and
     // U_eff as operands, so it costs them no LDS reads but Q), else the io waves.
+    // Register sets for the operands that come straight from global memory: two (two blocks of
+    // loads in flight) where the registers allow, else one.
+    constexpr int kSets = (N <= 128 && !(D == 128 && N == 128 && C == 128 && TV == 32)) ? 2 : 1;
     constexpr bool kStateReadout = RO && N <= 128;
     constexpr bool kIoReadout = RO && N > 128;
     static_assert(D % 64 == 0 && TV % 16 == 0 && N % 32 == 0, "tile shapes");
@@ -163,51 +166,69 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         constexpr auto tok_tile = [](int i) constexpr { return CT >= 8 ? ((i & 1) ? 8 * (i >> 1) + 7 - W : 8 * (i >> 1) + W) : W + 4 * i; };
         // (a chunk of fewer than 64 tokens has fewer tiles than waves: the waves beyond own none)
         constexpr auto ksteps_of = [](int tt) constexpr { return tt < CT ? (R * (16 * tt + 16) + 31) / 32 : 0; };
-        bf16x8 p2[T2][NKT];        // P tiles of this wave's token tiles (those the causal mask keeps)
-        auto fetch_p = [&](size_t cid) {
+        // Every operand that comes straight from global memory has two register sets: block ch
+        // uses set ch & 1 and, right after its last use, requests block ch + 2 into it, so that
+        // two blocks' worth of loads are in flight (one block's worth does not cover the latency
+        // of the memory system at the rate a CU can pull data in).
+        bf16x8 p2[kSets][T2][NKT]; // P tiles of this wave's token tiles (those the causal mask keeps)
+        auto fetch_p = [&](size_t cid, auto Sc) {
+            constexpr int S = decltype(Sc)::value % kSets;
             const bf16 *Pc = Pt + cid * (size_t)C * N;
 #pragma unroll
             for (int i = 0; i < T2; ++i) {
                 const int tt = tok_tile(i);
 #pragma unroll
                 for (int kt = 0; kt < NKT; ++kt)
-                    if (kt < ksteps_of(tt)) p2[i][kt] = ld8(Pc + ((size_t)(tt * NKT + kt) * 64 + lane) * 8);
+                    if (kt < ksteps_of(tt)) p2[S][i][kt] = ld8(Pc + ((size_t)(tt * NKT + kt) * 64 + lane) * 8);
             }
         };
 
         // Q of this wave's token tiles, straight from global memory in B-operand form (16 rows x
         // 64 bytes per load: only a few loads per step, so the poor coalescing does not matter)
-        bf16x8 bQ[T2][NKS];
-        auto fetch_q = [&](size_t cid) {
+        bf16x8 bQ[kSets][T2][NKS];
+        auto fetch_q = [&](size_t cid, auto Sc) {
+            constexpr int S = decltype(Sc)::value % kSets;
             const bf16 *Qc = Q + cid * (size_t)C * D;
 #pragma unroll
             for (int i = 0; i < T2; ++i)
 #pragma unroll
                 for (int ks = 0; ks < NKS; ++ks)
-                    if (tok_tile(i) < CT) bQ[i][ks] = ld8(Qc + (size_t)(16 * tok_tile(i) + r16) * D + 32 * ks + 8 * g);
+                    if (tok_tile(i) < CT) bQ[S][i][ks] = ld8(Qc + (size_t)(16 * tok_tile(i) + r16) * D + 32 * ks + 8 * g);
         };
 
-        bf16x8 t1[M1][NKT];        // T tiles of this wave's rows of U_eff (those below the diagonal)
-        auto fetch_t = [&](size_t cid) {
+        bf16x8 t1[kSets][M1][NKT]; // T tiles of this wave's rows of U_eff (those below the diagonal)
+        auto fetch_t = [&](size_t cid, auto Sc) {
+            constexpr int S = decltype(Sc)::value % kSets;
             const bf16 *Tc = Tt + cid * (size_t)N * N;
 #pragma unroll
             for (int i = 0; i < M1; ++i) {
                 const int mt = row_tile(i);
 #pragma unroll
                 for (int kt = 0; kt < NKT; ++kt)
-                    if (2 * kt <= mt) t1[i][kt] = ld8(Tc + ((size_t)(mt * NKT + kt) * 64 + lane) * 8);
+                    if (2 * kt <= mt) t1[S][i][kt] = ld8(Tc + ((size_t)(mt * NKT + kt) * 64 + lane) * 8);
             }
         };
+        constexpr std::integral_constant<int, 0> kSet0{};
+        constexpr std::integral_constant<int, 1> kSet1{};
         if (NC > 0) {
-            fetch_t(c0);
+            const size_t c1 = NC > 1 ? c0 + 1 : c0;
+            fetch_t(c0, kSet0);
             if constexpr (kStateReadout) {
-                fetch_p(c0);
-                fetch_q(c0);
+                fetch_p(c0, kSet0);
+                fetch_q(c0, kSet0);
+            }
+            if constexpr (kSets == 2) {
+                fetch_t(c1, kSet1);
+                if constexpr (kStateReadout) {
+                    fetch_p(c1, kSet1);
+                    fetch_q(c1, kSet1);
+                }
             }
         }
         __syncthreads();
 
-        for (int ch = 0; ch < NC; ++ch) {
+        auto step = [&](int ch, auto Pc) {
+            constexpr int PS = decltype(Pc)::value % kSets;   // register set of this block
             // The lane id is laundered once per step so that the per-lane LDS offsets of the
             // unrolled code below are recomputed where they are used instead of being hoisted
             // out of this loop and held in registers for the whole kernel.
@@ -215,7 +236,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             asm volatile("" : "+v"(lane));
             r16 = lane & 15; g = lane >> 4;
             const size_t cid = c0 + ch;
-            const size_t nx = ch + 1 < NC ? cid + 1 : cid;   // last step re-fetches its own chunk
+            const size_t nx = ch + kSets < NC ? cid + kSets : c0 + NC - 1;   // the last steps re-fetch the last block
             const bf16 *Kc = Ks + (kDoubleK ? (ch & 1) * N * KP : 0);
 
             // Each interval first issues every LDS read it needs and only then starts its MFMAs
@@ -278,9 +299,9 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 #pragma unroll
                         for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
-                            for (int md = 0; md < NNT; ++md) oacc[i][md] = mfma16(bS[md][ks], bQ[i][ks], oacc[i][md]);
+                            for (int md = 0; md < NNT; ++md) oacc[i][md] = mfma16(bS[md][ks], bQ[PS][i][ks], oacc[i][md]);
                     }
-                    fetch_q(nx);
+                    fetch_q(nx, Pc);
                 }
             }
             __syncthreads();
@@ -309,7 +330,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                     for (int kt = 0; kt < KMAX; ++kt) {
                         if (2 * kt <= mt) {
 #pragma unroll
-                            for (int nt = 0; nt < NNT; ++nt) acc[nt] = mfma16(t1[i][kt], bR[kt][nt], acc[nt]);
+                            for (int nt = 0; nt < NNT; ++nt) acc[nt] = mfma16(t1[PS][i][kt], bR[kt][nt], acc[nt]);
                         }
                     }
 #pragma unroll
@@ -321,7 +342,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                         st4(&Ue[(16 * nt + r16) * UP + 32 * (mt >> 1) + 8 * g + 4 * (mt & 1)], cvt4(acc[nt]));
                 }
             }
-            fetch_t(nx);
+            fetch_t(nx, Pc);
             __syncthreads();
 
             // ---- interval 2: S^T += K^T U_eff, this wave's d_k rows; K^T comes out of the
@@ -358,7 +379,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                                 if (k0 + kk < ksteps_of(tok_tile(i))) {
 #pragma unroll
                                     for (int md = 0; md < NNT; ++md)
-                                        oacc[i][md] = mfma16(b[kk][md], p2[i][k0 + kk], oacc[i][md]);
+                                        oacc[i][md] = mfma16(b[kk][md], p2[PS][i][k0 + kk], oacc[i][md]);
                                 }
                     }
                 }
@@ -374,10 +395,14 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 #pragma unroll
                     for (int md = 0; md < NNT; ++md)
                         if (tok_tile(i) < CT) st4(&Ob[(16 * tok_tile(i) + r16) * OP + 16 * md + 4 * g], cvt4(oacc[i][md]));
-                fetch_p(nx);
+                fetch_p(nx, Pc);
             }
             if (!kDoubleK) __syncthreads();   // interval 3: the io waves overwrite K in place
             __syncthreads();
+        };
+        for (int ch = 0; ch < NC; ch += 2) {
+            step(ch, kSet0);
+            if (ch + 1 < NC) step(ch + 1, kSet1);
         }
 
         if (SL) {
@@ -401,9 +426,12 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         constexpr int PPR = TV / 8;                                // 16-byte pieces per row of the V tile
         constexpr int VV = (N * PPR + NTHR - 1) / NTHR;            // vectors of the V tile per thread
         constexpr int OV = (C * PPR + NTHR - 1) / NTHR;            // vectors of the O tile per thread
-        bf16x8 kreg[KV], vreg[VV];
-        bf16 breg = (bf16)0.0f;
-        bf16x8 p2[T2][NKT];        // P tiles of this wave's token tiles (those the causal mask keeps)
+        // Two register sets, as in the state waves: block ch + 1 is staged into LDS during step ch
+        // out of set (ch + 1) & 1, which is then refilled with block ch + 3, so that two blocks of K,
+        // V tile and beta are on their way at any time.
+        bf16x8 kreg[kSets][KV], vreg[kSets][VV];
+        bf16 breg[kSets];
+        bf16x8 p2[kSets][T2][NKT]; // P tiles of this wave's token tiles (those the causal mask keeps)
 
         // token tiles of O owned by this wave: W and (with 8 tiles) 7 - W
         constexpr auto tok_tile = [](int i) constexpr { return CT >= 8 ? ((i & 1) ? 8 * (i >> 1) + 7 - W : 8 * (i >> 1) + W) : W + 4 * i; };
@@ -413,59 +441,65 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         // K moves in two halves (vectors [0, KH) and [KH, KV) of every thread) so that its
         // staging and load issue can be spread over two intervals
         constexpr int KH = KV / 2;
-        auto fetch_k = [&](size_t cid, int q0, int q1) {
+        auto fetch_k = [&](size_t cid, int q0, int q1, auto Sc) {
+            constexpr int S = decltype(Sc)::value % kSets;
             const bf16 *Kg = K + cid * (size_t)N * D;
 #pragma unroll
             for (int q = 0; q < KV; ++q) {
                 const int v = tb + NTHR * q;
-                if (q >= q0 && q < q1 && ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8)) kreg[q] = ld8(Kg + (size_t)v * 8);
+                if (q >= q0 && q < q1 && ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8)) kreg[S][q] = ld8(Kg + (size_t)v * 8);
             }
         };
-        auto fetch_vqb = [&](size_t cid) {
+        auto fetch_vqb = [&](size_t cid, auto Sc) {
+            constexpr int S = decltype(Sc)::value % kSets;
             const bf16 *Vg = V + (size_t)vmul * cid * (size_t)N * D + dv0;
 #pragma unroll
             for (int q = 0; q < VV; ++q) {
                 int v = tb + NTHR * q;
                 v = v < N * PPR ? v : N * PPR - 1;                 // clamp instead of branching
-                vreg[q] = ld8(Vg + (size_t)(v / PPR) * D + (v % PPR) * 8);
+                vreg[S][q] = ld8(Vg + (size_t)(v / PPR) * D + (v % PPR) * 8);
             }
-            breg = beta[cid * (size_t)N + (tb % N)];
+            breg[S] = beta[cid * (size_t)N + (tb % N)];
         };
-        auto fetch_p = [&](size_t cid) {
+        auto fetch_p = [&](size_t cid, auto Sc) {
+            constexpr int S = decltype(Sc)::value % kSets;
             const bf16 *Pc = Pt + cid * (size_t)C * N;
 #pragma unroll
             for (int i = 0; i < T2; ++i) {
                 const int tt = tok_tile(i);
 #pragma unroll
                 for (int kt = 0; kt < NKT; ++kt)
-                    if (kt < ksteps_of(tt)) p2[i][kt] = ld8(Pc + ((size_t)(tt * NKT + kt) * 64 + lane) * 8);
+                    if (kt < ksteps_of(tt)) p2[S][i][kt] = ld8(Pc + ((size_t)(tt * NKT + kt) * 64 + lane) * 8);
             }
         };
         // Q of this wave's token tiles, straight from global memory in B-operand form
-        bf16x8 bQ[T2][NKS];
-        auto fetch_q = [&](size_t cid) {
+        bf16x8 bQ[kSets][T2][NKS];
+        auto fetch_q = [&](size_t cid, auto Sc) {
+            constexpr int S = decltype(Sc)::value % kSets;
             const bf16 *Qc = Q + cid * (size_t)C * D;
 #pragma unroll
             for (int i = 0; i < T2; ++i)
 #pragma unroll
                 for (int ks = 0; ks < NKS; ++ks)
-                    if (tok_tile(i) < CT) bQ[i][ks] = ld8(Qc + (size_t)(16 * tok_tile(i) + r16) * D + 32 * ks + 8 * g);
+                    if (tok_tile(i) < CT) bQ[S][i][ks] = ld8(Qc + (size_t)(16 * tok_tile(i) + r16) * D + 32 * ks + 8 * g);
         };
-        auto stage_k = [&](bf16 *Kd, int q0, int q1) {
+        auto stage_k = [&](bf16 *Kd, int q0, int q1, auto Sc) {
+            constexpr int S = decltype(Sc)::value % kSets;
 #pragma unroll
             for (int q = 0; q < KV; ++q) {
                 const int v = tb + NTHR * q;
                 if (q >= q0 && q < q1 && ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8))
-                    st8(&Kd[(v / VPR) * KP + (v % VPR) * 8], kreg[q]);
+                    st8(&Kd[(v / VPR) * KP + (v % VPR) * 8], kreg[S][q]);
             }
         };
-        auto stage_vqb = [&]() {
+        auto stage_vqb = [&](auto Sc) {
+            constexpr int S = decltype(Sc)::value % kSets;
 #pragma unroll
             for (int q = 0; q < VV; ++q) {
                 const int v = tb + NTHR * q;
-                if (v < N * PPR) st8(&Vs[(v / PPR) * VP + (v % PPR) * 8], vreg[q]);
+                if (v < N * PPR) st8(&Vs[(v / PPR) * VP + (v % PPR) * 8], vreg[S][q]);
             }
-            if (tb < N) bs[tb] = (float)breg;
+            if (tb < N) bs[tb] = (float)breg[S];
         };
         // the O tile of one chunk (chunk tokens x TV features), LDS -> its rows of O
         auto copy_out = [&](size_t cid) {
@@ -479,28 +513,42 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             }
         };
 
+        constexpr std::integral_constant<int, 0> kSet0{};
+        constexpr std::integral_constant<int, 1> kSet1{};
         if (NC > 0) {
-            fetch_k(c0, 0, KV);
-            fetch_vqb(c0);
+            const size_t last = c0 + NC - 1;
+            const size_t c1 = NC > 1 ? c0 + 1 : last, c2 = NC > 2 ? c0 + 2 : last;
+            fetch_k(c0, 0, KV, kSet0);
+            fetch_vqb(c0, kSet0);
             if constexpr (kIoReadout) {
-                fetch_p(c0);
-                fetch_q(c0);
+                fetch_p(c0, kSet0);
+                fetch_q(c0, kSet0);
+                if constexpr (kSets == 2) {
+                    fetch_p(c1, kSet1);
+                    fetch_q(c1, kSet1);
+                }
             }
-            stage_k(Ks, 0, KV);
-            stage_vqb();
-            const size_t c1 = NC > 1 ? c0 + 1 : c0;
-            fetch_k(c1, 0, KV);
-            fetch_vqb(c1);
+            if constexpr (kSets == 2) {
+                fetch_k(c1, 0, KV, kSet1);
+                fetch_vqb(c1, kSet1);
+            }
+            stage_k(Ks, 0, KV, kSet0);
+            stage_vqb(kSet0);
+            // with one set: block 1 now; with two: block 2 (block 1 is already on its way)
+            fetch_k(kSets == 2 ? c2 : c1, 0, KV, kSet0);
+            fetch_vqb(kSets == 2 ? c2 : c1, kSet0);
         }
         __syncthreads();
 
-        for (int ch = 0; ch < NC; ++ch) {
+        auto step = [&](int ch, auto Pc) {
+            constexpr int PS = decltype(Pc)::value % kSets;                          // set of block ch
+            constexpr std::integral_constant<int, (decltype(Pc)::value + 1) % kSets> Nc{};   // set that holds block ch + 1
             tb = tb0;
             asm volatile("" : "+v"(tb));
             lane = tb & 63; r16 = lane & 15; g = lane >> 4;
             const size_t cid = c0 + ch;
-            const size_t n1 = ch + 1 < NC ? cid + 1 : cid;          // chunk held in registers
-            const size_t n2 = ch + 2 < NC ? cid + 2 : c0 + NC - 1;  // chunk to request next
+            const size_t n2 = ch + kSets < NC ? cid + kSets : c0 + NC - 1;          // block to request into this block's set
+            const size_t n3 = ch + 1 + kSets < NC ? cid + 1 + kSets : c0 + NC - 1;  // ... into the next block's set
 
             // ---- interval 0: previous O tile out; O^T = S Q^T for this wave's token tiles; first
             // half of the next chunk's K into the buffer this step does not read
@@ -521,21 +569,21 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 #pragma unroll
                     for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
-                        for (int md = 0; md < NNT; ++md) oacc[i][md] = mfma16(aS[md][ks], bQ[i][ks], oacc[i][md]);
+                        for (int md = 0; md < NNT; ++md) oacc[i][md] = mfma16(aS[md][ks], bQ[PS][i][ks], oacc[i][md]);
                 }
-                fetch_q(n1);
+                fetch_q(n2, Pc);
             }
             bf16 *Knext = Ks + (kDoubleK ? ((ch + 1) & 1) * N * KP : 0);
             if (kDoubleK) {
-                stage_k(Knext, 0, KH);
-                fetch_k(n2, 0, KH);
+                stage_k(Knext, 0, KH, Nc);
+                fetch_k(n3, 0, KH, Nc);
             }
             __syncthreads();
 
-            // ---- interval 1: next chunk's V tile and beta registers -> LDS, the chunk after it on
-            // its way
-            stage_vqb();
-            fetch_vqb(n2);
+            // ---- interval 1: next chunk's V tile and beta registers -> LDS, the chunk after the
+            // one after it on its way
+            stage_vqb(Nc);
+            fetch_vqb(n3, Nc);
             __syncthreads();
 
             // ---- interval 2: O^T += U_eff^T P^T, O tile to LDS
@@ -558,24 +606,28 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                     for (int kt = 0; kt < KM; ++kt)
                         if (kt < ksteps_of(tt)) {
 #pragma unroll
-                            for (int md = 0; md < NNT; ++md) oacc[i][md] = mfma16(aU[kt][md], p2[i][kt], oacc[i][md]);
+                            for (int md = 0; md < NNT; ++md) oacc[i][md] = mfma16(aU[kt][md], p2[PS][i][kt], oacc[i][md]);
                         }
 #pragma unroll
                     for (int md = 0; md < NNT; ++md)
                         st4(&Ob[(16 * tt + r16) * OP + 16 * md + 4 * g], cvt4(oacc[i][md]));
                 }
             }
-            if constexpr (kIoReadout) fetch_p(n1);
+            if constexpr (kIoReadout) fetch_p(n2, Pc);
             if (kDoubleK) {
-                stage_k(Knext, KH, KV);
-                fetch_k(n2, KH, KV);
+                stage_k(Knext, KH, KV, Nc);
+                fetch_k(n3, KH, KV, Nc);
             } else {
                 // ---- interval 3: K of the next chunk replaces this chunk's in place
                 __syncthreads();
-                stage_k(Ks, 0, KV);
-                fetch_k(n2, 0, KV);
+                stage_k(Ks, 0, KV, Nc);
+                fetch_k(n3, 0, KV, Nc);
             }
             __syncthreads();
+        };
+        for (int ch = 0; ch < NC; ch += 2) {
+            step(ch, kSet0);
+            if (ch + 1 < NC) step(ch + 1, kSet1);
         }
         if (NC > 0) copy_out(c0 + NC - 1);
     };
