@@ -14,12 +14,12 @@
 //
 //   state waves (0..3)  run the chain: R (interval 0), U_eff (interval 1), S update (interval 2).
 //                       Their global loads are their own T tiles, straight into MFMA operand
-//                       registers, one chunk ahead.  For n <= 128 they also compute O: S and
+//                       registers, two chunks ahead (n <= 128; one for n = 256).  For n <= 128 they also compute O: S and
 //                       U_eff are already in their registers as operands of the chain, and Q
 //                       of a wave's token tiles is loaded straight into operand registers,
 //                       so Q S^T and U_eff^T P^T cost no LDS reads.
 //   io waves (4..7)     do everything that can be late or early: staging of the next chunk's K,
-//                       V tile, beta from registers into LDS and the loads of the chunk after
+//                       V tile, beta from registers into LDS and the loads of the chunks after
 //                       it (spread over the intervals), the coalesced copy of the previous O tile
 //                       to global memory, and for n = 256 (where the state waves have no
 //                       registers to spare) Q S^T (interval 0) and U_eff^T P^T (interval 2).
