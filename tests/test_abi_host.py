@@ -237,3 +237,33 @@ def test_beta_exponential_checks(pf):
     assert f(p, p, p, 1, 1, 8, 16, 1, 3, 0) == pf.PF_ERR_UNSUPPORTED
     assert f(p + 2, p, p, 1, 1, 8, 16, 1, pf.PF_BF16, 0) == pf.PF_ERR_ALIGN
     assert f(None, None, None, 1, 1, 0, 16, 1, pf.PF_BF16, 0) == pf.PF_OK     # empty sequence
+
+
+def test_header_is_plain_c(pf, tmp_path):
+    """include/pf.h compiles as C99 with -pedantic -Werror, and a C program linked against libpf.so
+    can call the host-only entry points (no C++ types cross the boundary)."""
+    import subprocess
+    src = tmp_path / "use_pf.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "pf.h"
+int main(void)
+{
+    pf_dtype dt = PF_BF16;
+    pf_stream s = NULL;
+    (void)s;
+    printf("%d %s %d %d %lu\n", pf_version(), pf_status_str(PF_ERR_ALIGN),
+           pf_delta_fwd_supported(128, 128, 2, 64, dt), pf_delta_fwd_block(128, 128, 4, 128, dt),
+           (unsigned long)pf_delta_fwd_workspace_bytes(4, 16, 4096, 128, 128, 2, 64, dt));
+    /* every check fails before a launch: NULL inputs */
+    return pf_delta_fwd(NULL, NULL, NULL, NULL, NULL, NULL, NULL, 1, 1, 64, 128, 128, 2, 64, dt, NULL, 0, NULL) == PF_ERR_NULL ? 0 : 1;
+}
+''')
+    exe = tmp_path / "use_pf"
+    libdir = os.path.dirname(LIB)
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-lpf", f"-Wl,-rpath,{libdir}", "-Wl,-rpath,/opt/rocm/lib"],
+                   check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert int(out[0]) == pf.pf_version()
+    assert out[-3:] == ["2", "32", str(pf.pf_delta_fwd_workspace_bytes(4, 16, 4096, 128, 128, 2, 64, pf.PF_BF16))]
