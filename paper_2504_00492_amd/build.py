@@ -12,7 +12,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpf.so")
-SOURCES = ["pf_api.hip", "pf_generic.hip", "pf_flow.hip", "pf_scan.hip", "pf_segments.hip", "pf_sigdelta.hip", "pf_rescale.hip"]
+SOURCES = ["pf_api.hip", "pf_generic.hip", "pf_flow.hip", "pf_scan.hip", "pf_fused.hip", "pf_segments.hip", "pf_sigdelta.hip", "pf_rescale.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # Packed-fp32 VALU forms are switched off for every kernel of this library.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-value",
@@ -28,7 +28,7 @@ def _compile(src: str) -> str:
 
 def build_library(verbose: bool = False) -> str:
     """Compile every source and link libpf.so.  Always recompiles."""
-    with ThreadPoolExecutor(max_workers=min(7, len(SOURCES))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     if verbose:

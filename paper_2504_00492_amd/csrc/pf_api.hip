@@ -2,9 +2,32 @@
 #include "../../include/pf.h"
 #include "pf_internal.h"
 
+#include <atomic>
+
+namespace pf {
+
+int device_cu_count()
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cached[kMaxDevices];   // 0: not asked yet
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n > 0) return n;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+    cached[dev].store(n, std::memory_order_relaxed);
+    return n;
+}
+
+}  // namespace pf
+
 namespace {
 
 constexpr size_t kAlign = 256;
+// The fused kernel (flow built inside the scan workgroup) reads and writes only q, k, v, beta, o,
+// but every d_v tile of a head repeats the flow of every block: measured slower than the two
+// kernels on every benchmark shape, so pf_delta_fwd does not take it.
+constexpr bool kUseFused = false;
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -194,9 +217,14 @@ static pf_status delta_fwd_impl(const void *Q, const void *K, const void *V, con
     {
         float *Smid = tail ? reinterpret_cast<float *>(ws + wp.oS) : S_L;
         const void *Tt = ws + wp.oT, *Pt = ws + wp.oP;
-        hipError_t e = pf::launch_chunk_flow(Q, K, beta, ws + wp.oT, ws + wp.oP, heads, L, d_k, r, block, s, product);
-        if (e != hipSuccess) return PF_ERR_LAUNCH;
-        if (wp.segments > 1) {
+        hipError_t e = hipSuccess;
+        if (kUseFused && wp.segments == 1 && pf::fused_instance_exists(d_k, block * r, block)) {
+            // flow and scan of every block in one kernel: T and P stay on chip
+            e = pf::launch_fused(Q, K, V, beta, S0, O, Smid, nullptr, nullptr, heads, L, d_k, r, block, product, s);
+            if (e != hipSuccess) return PF_ERR_LAUNCH;
+        } else if (wp.segments > 1) {
+            e = pf::launch_chunk_flow(Q, K, beta, ws + wp.oT, ws + wp.oP, heads, L, d_k, r, block, s, product);
+            if (e != hipSuccess) return PF_ERR_LAUNCH;
             // Segment-parallel scan (no tail here): every segment of every head is a chain of
             // its own.  What a segment does to a zero state, then its propagator (identity in,
             // zero values), then the composition over the segments of a head, then the real
@@ -214,9 +242,12 @@ static pf_status delta_fwd_impl(const void *Q, const void *K, const void *V, con
             if (e != hipSuccess) return PF_ERR_LAUNCH;
             e = pf::launch_chunk_scan(Q, K, V, beta, Tt, Pt, Sin, O, nullptr, vh, Ls, d_k, r, block, s);
             return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+        } else {
+            e = pf::launch_chunk_flow(Q, K, beta, ws + wp.oT, ws + wp.oP, heads, L, d_k, r, block, s, product);
+            if (e != hipSuccess) return PF_ERR_LAUNCH;
+            e = pf::launch_chunk_scan(Q, K, V, beta, Tt, Pt, S0, O, Smid, heads, L, d_k, r, block, s);
+            if (e != hipSuccess) return PF_ERR_LAUNCH;
         }
-        e = pf::launch_chunk_scan(Q, K, V, beta, ws + wp.oT, ws + wp.oP, S0, O, Smid, heads, L, d_k, r, block, s);
-        if (e != hipSuccess) return PF_ERR_LAUNCH;
         state = Smid;
     }
     if (tail) {

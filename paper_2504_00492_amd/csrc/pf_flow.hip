@@ -21,7 +21,7 @@
 //
 // Work split.  The n columns of X (= rows of T) are dealt to the waves in 16-column slices; a
 // wave keeps the finished blocks X_i of its slices in registers, already in B-operand form (see
-// pf_common.cuh), so the substitution needs no LDS traffic for X.  G^T block-columns and T_jj^T
+// pf_common.h), so the substitution needs no LDS traffic for X.  G^T block-columns and T_jj^T
 // are built cooperatively and read by all waves as A operands from LDS.  P = Mbar (.) Q K^T
 // (readout mask, inclusive in time) is computed from the same resident K.
 //
@@ -30,7 +30,7 @@
 //
 // Outputs: the tiled operand arrays Tt and Pt described in pf_layout.h.
 #include "pf_internal.h"
-#include "pf_common.cuh"
+#include "pf_common.h"
 #include "pf_layout.h"
 
 #include <atomic>
@@ -396,7 +396,7 @@ static hipError_t launch_flow_instance(const void *Q, const void *K, const void 
     // Persistent grid: as many workgroups as the chip holds at once (LDS decides how many per
     // CU, at most two), each walking its share of the chunks.
     const size_t per_cu = kMaxLdsBytes / lds ? kMaxLdsBytes / lds : 1;
-    const size_t resident = kNumCUs * (per_cu > 2 ? 2 : per_cu);
+    const size_t resident = (size_t)device_cu_count() * (per_cu > 2 ? 2 : per_cu);
     const unsigned grid = (unsigned)(nchunks < resident ? nchunks : resident);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kFlowThreads), lds, stream, (const bf16 *)Q,
                        (const bf16 *)K, (const bf16 *)beta, (bf16 *)Tt, (bf16 *)Pt, (int)nchunks, NC, tail, mask_shift);

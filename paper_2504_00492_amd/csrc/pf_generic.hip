@@ -16,7 +16,7 @@
 // by loading (K, beta K, beta V) := (-B, A, -Atil): Theorem 3.2's Id - M (.) A B^T is then
 // Id + M (.) (A)(-B)^T, its U + W S_0^T is -(U_eff), and every later line is unchanged.
 #include "pf_internal.h"
-#include "pf_common.cuh"
+#include "pf_common.h"
 
 namespace pf {
 

@@ -8,7 +8,10 @@
 namespace pf {
 
 constexpr size_t kMaxLdsBytes = 160 * 1024;  // LDS per workgroup (and per CU) on gfx950
-constexpr size_t kNumCUs = 256;              // compute units of one MI355X
+
+// Compute units of the current device (asked once per device, then cached); 256, the count of
+// an MI355X, when no device answers (host-only callers).
+int device_cu_count();
 
 // ---- generic path (pf_generic.hip)
 size_t generic_lds_bytes(int dk, int dv, int r, int chunk);
@@ -36,6 +39,15 @@ hipError_t launch_chunk_scan(const void *Q, const void *K, const void *V, const 
 // (O may be NULL: the state is advanced and S_L written, nothing is read out.)
 // d_v rows of S one scan workgroup owns for these dimensions (the scan runs heads * d / tile chains)
 int scan_dv_tile(int heads, int d, int n);
+
+// ---- fused forward (pf_fused.hip): flow and scan of every block in one kernel, d = d_k = d_v,
+// n = chunk * r in {64, 128}.  Takes the first L / chunk whole blocks of every head.  Tdump / Pdump
+// (may be NULL) receive T and P of every block in the layout of the split entry points.
+bool fused_instance_exists(int d, int n, int chunk);
+int fused_dv_tile(int heads, int d, int n, int chunk);
+hipError_t launch_fused(const void *Q, const void *K, const void *V, const void *beta, const float *S0, void *O,
+                        float *SL, void *Tdump, void *Pdump, int heads, int L, int d, int r, int chunk,
+                        bool product, hipStream_t stream);
 
 // ---- segment-parallel scan (pf_segments.hip): S0 / V constants and the composition of segments
 // writes an n x d block of bf16 zeros at zeroV and the d x d fp32 identity at ident

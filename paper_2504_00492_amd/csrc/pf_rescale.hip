@@ -5,7 +5,7 @@
 // One row of K per 16 lanes: 16-byte loads where the row length allows, partial sums combined
 // with DPP shuffles inside the 16-lane row, fp32 arithmetic.
 #include "pf_internal.h"
-#include "pf_common.cuh"
+#include "pf_common.h"
 
 namespace pf {
 

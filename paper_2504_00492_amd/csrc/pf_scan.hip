@@ -42,7 +42,7 @@
 // compile time, leaving straight-line code in which LDS reads can be scheduled ahead of the
 // MFMAs that use them.  Every fetch is unconditional, the last step re-fetches its own chunk.
 #include "pf_internal.h"
-#include "pf_common.cuh"
+#include "pf_common.h"
 #include "pf_layout.h"
 
 #include <atomic>

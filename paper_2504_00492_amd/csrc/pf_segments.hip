@@ -12,7 +12,7 @@
 // kernels here provide those two constants and the composition over the segments of a head;
 // a last pass of the scan kernel then runs every segment from its true incoming state.
 #include "pf_internal.h"
-#include "pf_common.cuh"
+#include "pf_common.h"
 
 namespace pf {
 

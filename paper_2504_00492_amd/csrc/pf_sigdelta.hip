@@ -28,7 +28,7 @@
 // kernel (MFMA for bf16 inputs) fills first; they do not depend on the sweep and are prefetched
 // one step ahead.
 #include "pf_internal.h"
-#include "pf_common.cuh"
+#include "pf_common.h"
 
 namespace pf {
 
