@@ -93,6 +93,18 @@ int pf_delta_fwd_block(int d_k, int d_v, int r, int chunk, pf_dtype dt);
 size_t pf_delta_fwd_workspace_bytes(int B, int H, int L, int d_k, int d_v, int r, int chunk,
                                     pf_dtype dt);
 
+/* Which kernels one pf_delta_fwd (or pf_delta_product_fwd) call with these dimensions enqueues, in
+ * launch order: the names of the kernel instantiations as a profiler prints them (template
+ * arguments included, parameter lists left out), separated by ';', e.g.
+ * "pf::flow_kernel<128, 128, 64>;pf::scan_kernel<128, 128, 64, 32, true>".  The scan kernel's last
+ * two arguments are the d_v rows one workgroup owns and whether it reads out O.  At most cap - 1
+ * characters and a terminating NUL are written to buf (buf may be NULL); the return value is the
+ * length of the whole description (0 for unsupported or invalid dimensions).  Depends on the
+ * compute-unit count of the current device where the d_v tile does (256 when no device answers).
+ * Meant for profiles and benchmarks that must name what they measured.  Host only. */
+size_t pf_delta_fwd_describe(int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt,
+                             char *buf, size_t cap);
+
 /*
  * Chunked forward of the rank-r delta rule (problem statement: Sections 1.1, 1.3, 3.1;
  * method: Section 3 steps 1-3 and Theorem 3.2).
@@ -213,6 +225,10 @@ pf_status pf_delta_chunk_flow(const void *Q, const void *K, const void *beta, vo
                               int B, int H, int L, int d_k, int d_v, int r, int chunk,
                               pf_stream stream);
 
+/* 1 when pf_delta_chunk_flow and pf_delta_chunk_scan have a kernel instance for these dimensions
+ * (the list above), else 0.  Host only. */
+int pf_delta_chunk_supported(int d_k, int d_v, int r, int chunk);
+
 /*
  * Step 3 of Section 3 fused with the readout, MFMA path only: hands the state from chunk to
  * chunk and reads out inside each chunk, from the inputs and the arrays pf_delta_chunk_flow wrote:
@@ -227,6 +243,27 @@ pf_status pf_delta_chunk_scan(const void *Q, const void *K, const void *V, const
                               const void *Tt, const void *Pt, const float *S0, void *O, float *S_L,
                               int B, int H, int L, int d_k, int d_v, int r, int chunk,
                               pf_stream stream);
+
+/*
+ * Steps 2 and 3 of Section 3 in ONE kernel, for callers without scratch memory: the flow of a
+ * block (T and P of Theorem 3.2) is built inside the workgroup that scans the block and never
+ * leaves the compute unit, so there is no workspace and device memory sees Q, K, V, beta once
+ * and O once.  The price: every d_v tile of a (b, h) repeats the block's flow for itself, which
+ * on MI355X costs more time than the workspace traffic it saves; pf_delta_fwd therefore uses
+ * the two kernels of pf_delta_chunk_flow / pf_delta_chunk_scan and is the faster call wherever
+ * a workspace can be had.
+ *
+ * MFMA path only (PF_BF16): d_k = d_v in {64, 128} and (chunk * r, chunk) one of (64, 64),
+ * (64, 32), (128, 32), (128, 64), (128, 128) (pf_delta_fwd_fused_supported returns 1), else
+ * PF_ERR_UNSUPPORTED.  The chunk is used as given (no halving); L must be a multiple of chunk
+ * (PF_ERR_SHAPE otherwise), L == 0 as for pf_delta_fwd.  product = 0 computes pf_delta_fwd,
+ * product != 0 pf_delta_product_fwd.  Q, K, V, beta, S0, O, S_L, stream, errors: as there.
+ */
+int pf_delta_fwd_fused_supported(int d_k, int d_v, int r, int chunk);
+pf_status pf_delta_fwd_fused(const void *Q, const void *K, const void *V, const void *beta,
+                             const float *S0, void *O, float *S_L,
+                             int B, int H, int L, int d_k, int d_v, int r, int chunk, int product,
+                             pf_stream stream);
 
 /*
  * Step 2 of Section 3 by the paper's second construction (Theorem 3.4): W and U of every chunk

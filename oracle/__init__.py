@@ -8,6 +8,8 @@ package imports nothing from the product package.
                        discretised dynamics, delta mapping of the Remark in Section 3.1), plain C.
                        ``delta_product_fwd`` (product form of the rank-r transition, the contrast
                        case) is that same routine on the sequence of L*r virtual tokens.
+                       ``delta_compare`` runs that recurrence per head and returns only error sums
+                       against a candidate result (every head of a full-size workload).
 * ``chunk_flow_ref.py`` numpy fp64 transcription of the chunk flow (Theorem 3.2, Proposition 3.3,
                        Theorem 3.4); used by the tests only, to pin the recurrence from a second,
                        independent direction.
@@ -49,6 +51,8 @@ def _load():
         lib.pf_oracle_flow_head.argtypes = [dp, dp, dp, dp, dp, dp, dp] + [ctypes.c_int] * 4
         lib.pf_oracle_delta_fwd.restype = ctypes.c_int
         lib.pf_oracle_delta_fwd.argtypes = [fp, fp, fp, fp, fp, dp, dp] + [ctypes.c_int] * 6
+        lib.pf_oracle_delta_compare.restype = ctypes.c_int
+        lib.pf_oracle_delta_compare.argtypes = [fp] * 7 + [dp] * 5 + [ctypes.c_int] * 6
         lib.pf_oracle_max_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -119,6 +123,38 @@ def delta_fwd(Q, K, V, beta, S0=None, want_O=True, nthreads=0):
     if rc != 0:
         raise MemoryError("pf_oracle_delta_fwd")
     return O, SL
+
+
+def delta_compare(Q, K, V, beta, S0, O_cand, SL_cand=None, nthreads=0):
+    """Hold a candidate result against the recurrence, head by head, without keeping the fp64
+    outputs: runs ``delta_fwd`` per head inside the C library and returns only sums.
+
+    Inputs as for ``delta_fwd`` with ONE leading axis N (heads); O_cand [N, L, dv] and
+    SL_cand [N, dv, dk] (or None) are the candidate's outputs as float32.
+    Returns a dict of float64 arrays: err2 [N, L] = |o_t(cand) - o_t|^2, ref2 [N, L] = |o_t|^2,
+    maxabs [N], and s_err2 [N], s_ref2 [N] for the final state (None without SL_cand)."""
+    K = np.ascontiguousarray(K, dtype=np.float32)
+    V = np.ascontiguousarray(V, dtype=np.float32)
+    Q = np.ascontiguousarray(Q, dtype=np.float32)
+    beta = np.ascontiguousarray(beta, dtype=np.float32)
+    N, L, R, dk = K.shape
+    dv = V.shape[-1]
+    assert V.shape == (N, L, R, dv) and Q.shape == (N, L, dk) and beta.shape == (N, L, R)
+    S0c = None if S0 is None else np.ascontiguousarray(S0, dtype=np.float32)
+    assert S0c is None or S0c.shape == (N, dv, dk)
+    Oc = np.ascontiguousarray(O_cand, dtype=np.float32)
+    assert Oc.shape == (N, L, dv)
+    Sc = None if SL_cand is None else np.ascontiguousarray(SL_cand, dtype=np.float32)
+    assert Sc is None or Sc.shape == (N, dv, dk)
+    err2 = np.zeros((N, L)); ref2 = np.zeros((N, L)); maxabs = np.zeros(N)
+    s_err2 = np.zeros(N); s_ref2 = np.zeros(N)
+    rc = _load().pf_oracle_delta_compare(_fptr(Q), _fptr(K), _fptr(V), _fptr(beta), _fptr(S0c), _fptr(Oc), _fptr(Sc),
+                                         _dptr(err2), _dptr(ref2), _dptr(maxabs), _dptr(s_err2), _dptr(s_ref2),
+                                         N, L, R, dk, dv, int(nthreads))
+    if rc != 0:
+        raise MemoryError("pf_oracle_delta_compare")
+    return dict(err2=err2, ref2=ref2, maxabs=maxabs, s_err2=None if Sc is None else s_err2,
+                s_ref2=None if Sc is None else s_ref2)
 
 
 def delta_product_fwd(Q, K, V, beta, S0=None, want_O=True, nthreads=0):

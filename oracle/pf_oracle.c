@@ -132,6 +132,71 @@ int pf_oracle_delta_fwd(const float *Q, const float *K, const float *V, const fl
     return status;
 }
 
+/* The same batched delta form, held against a candidate result instead of being returned: for
+ * every head the recurrence above is run as it stands, and the candidate's O (float, [N][L][dv])
+ * and final state (float, [N][dv][dk], may be NULL) are compared with it token by token.  Only
+ * sums come back, so every head of a full-size workload can be checked without keeping the
+ * fp64 outputs of all of them:
+ *   err2 [N][L]   |o_t(candidate) - o_t|^2        ref2 [N][L]   |o_t|^2
+ *   maxabs [N]    max over (t, m) of |o_t(candidate)[m] - o_t[m]|
+ *   s_err2 [N], s_ref2 [N]   the same two sums over the final state (untouched if SLc is NULL)
+ * No arithmetic of the method lives here: pf_oracle_flow_head produces the reference.
+ * Returns 0 on success, -1 on allocation failure. */
+int pf_oracle_delta_compare(const float *Q, const float *K, const float *V, const float *beta,
+                            const float *S0, const float *Oc, const float *SLc,
+                            double *err2, double *ref2, double *maxabs, double *s_err2, double *s_ref2,
+                            int N, int L, int R, int dk, int dv, int nthreads)
+{
+    int status = 0;
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+#else
+    (void)nthreads;
+#endif
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int h = 0; h < N; ++h) {
+        const size_t no = (size_t)L * dv, ns = (size_t)dv * dk;
+        double *O  = (double *)malloc(sizeof(double) * (no ? no : 1));
+        double *SL = (double *)malloc(sizeof(double) * ns);
+        int rc = (O && SL) ? 0 : -1;
+        if (rc == 0)
+            rc = pf_oracle_delta_fwd(Q + (size_t)h * L * dk, K + (size_t)h * L * R * dk, V + (size_t)h * L * R * dv,
+                                     beta + (size_t)h * L * R, S0 ? S0 + h * ns : NULL, O, SL, 1, L, R, dk, dv, -1);
+        if (rc != 0) {
+#pragma omp atomic write
+            status = -1;
+        } else {
+            double worst = 0.0;
+            for (int t = 0; t < L; ++t) {
+                double e2 = 0.0, r2 = 0.0;
+                for (int m = 0; m < dv; ++m) {
+                    const double ref = O[(size_t)t * dv + m];
+                    const double dif = (double)Oc[(size_t)h * no + (size_t)t * dv + m] - ref;
+                    e2 += dif * dif;
+                    r2 += ref * ref;
+                    if (dif > worst) worst = dif;
+                    if (-dif > worst) worst = -dif;
+                }
+                err2[(size_t)h * L + t] = e2;
+                ref2[(size_t)h * L + t] = r2;
+            }
+            maxabs[h] = worst;
+            if (SLc) {
+                double e2 = 0.0, r2 = 0.0;
+                for (size_t i = 0; i < ns; ++i) {
+                    const double dif = (double)SLc[h * ns + i] - SL[i];
+                    e2 += dif * dif;
+                    r2 += SL[i] * SL[i];
+                }
+                s_err2[h] = e2;
+                s_ref2[h] = r2;
+            }
+        }
+        free(O); free(SL);
+    }
+    return status;
+}
+
 int pf_oracle_max_threads(void)
 {
 #ifdef _OPENMP

@@ -14,7 +14,7 @@ PF_OK, PF_ERR_NULL, PF_ERR_SHAPE, PF_ERR_UNSUPPORTED, PF_ERR_ALIGN, PF_ERR_WORKS
 PF_F32, PF_BF16 = 0, 1
 
 EXPORTS = ["pf_version", "pf_status_str", "pf_delta_fwd_supported", "pf_delta_fwd_block", "pf_delta_fwd_workspace_bytes",
-           "pf_delta_fwd", "pf_delta_product_fwd", "pf_beta_exponential", "pf_flow_fwd_supported", "pf_flow_fwd", "pf_delta_chunk_flow", "pf_delta_chunk_scan",
+           "pf_delta_fwd_describe", "pf_delta_fwd", "pf_delta_product_fwd", "pf_delta_fwd_fused_supported", "pf_delta_fwd_fused", "pf_beta_exponential", "pf_flow_fwd_supported", "pf_flow_fwd", "pf_delta_chunk_supported", "pf_delta_chunk_flow", "pf_delta_chunk_scan",
            "pf_delta_chunk_sigdelta_supported", "pf_delta_chunk_sigdelta_workspace_bytes", "pf_delta_chunk_sigdelta"]
 
 
@@ -40,16 +40,24 @@ def _load() -> ctypes.CDLL:
     lib.pf_delta_fwd_block.argtypes = [i, i, i, i, i]
     lib.pf_delta_fwd_workspace_bytes.restype = sz
     lib.pf_delta_fwd_workspace_bytes.argtypes = [i] * 8
+    lib.pf_delta_fwd_describe.restype = sz
+    lib.pf_delta_fwd_describe.argtypes = [i] * 8 + [ctypes.c_char_p, sz]
     lib.pf_delta_fwd.restype = i
     lib.pf_delta_fwd.argtypes = [vp] * 7 + [i] * 8 + [vp, sz, vp]
     lib.pf_delta_product_fwd.restype = i
     lib.pf_delta_product_fwd.argtypes = [vp] * 7 + [i] * 8 + [vp, sz, vp]
+    lib.pf_delta_fwd_fused_supported.restype = i
+    lib.pf_delta_fwd_fused_supported.argtypes = [i] * 4
+    lib.pf_delta_fwd_fused.restype = i
+    lib.pf_delta_fwd_fused.argtypes = [vp] * 7 + [i] * 8 + [vp]
     lib.pf_beta_exponential.restype = i
     lib.pf_beta_exponential.argtypes = [vp] * 3 + [i] * 6 + [vp]
     lib.pf_flow_fwd_supported.restype = i
     lib.pf_flow_fwd_supported.argtypes = [i, i, i, i, i]
     lib.pf_flow_fwd.restype = i
     lib.pf_flow_fwd.argtypes = [vp] * 7 + [i] * 8 + [vp]
+    lib.pf_delta_chunk_supported.restype = i
+    lib.pf_delta_chunk_supported.argtypes = [i] * 4
     lib.pf_delta_chunk_flow.restype = i
     lib.pf_delta_chunk_flow.argtypes = [vp] * 5 + [i] * 7 + [vp]
     lib.pf_delta_chunk_scan.restype = i
@@ -104,6 +112,16 @@ def pf_delta_fwd_workspace_bytes(B, H, L, d_k, d_v, r, chunk, dt) -> int:
     return int(_lib.pf_delta_fwd_workspace_bytes(B, H, L, d_k, d_v, r, chunk, dt))
 
 
+def pf_delta_fwd_describe(B, H, L, d_k, d_v, r, chunk, dt) -> list:
+    """Kernel instantiations one pf_delta_fwd call enqueues, in launch order (list of names)."""
+    need = int(_lib.pf_delta_fwd_describe(B, H, L, d_k, d_v, r, chunk, dt, None, 0))
+    if need == 0:
+        return []
+    buf = ctypes.create_string_buffer(need + 1)
+    _lib.pf_delta_fwd_describe(B, H, L, d_k, d_v, r, chunk, dt, buf, need + 1)
+    return buf.value.decode().split(";")
+
+
 def pf_delta_fwd(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, workspace, workspace_bytes,
                  stream=None) -> int:
     """Raw call; returns the pf_status.  Pointers may be torch tensors, ints or None."""
@@ -120,6 +138,16 @@ def pf_delta_product_fwd(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk,
                                          _stream_handle(stream)))
 
 
+def pf_delta_fwd_fused_supported(d_k, d_v, r, chunk) -> int:
+    return int(_lib.pf_delta_fwd_fused_supported(d_k, d_v, r, chunk))
+
+
+def pf_delta_fwd_fused(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, product=0, stream=None) -> int:
+    """Raw call; returns the pf_status.  Pointers may be torch tensors, ints or None."""
+    return int(_lib.pf_delta_fwd_fused(_ptr(Q), _ptr(K), _ptr(V), _ptr(beta), _ptr(S0), _ptr(O), _ptr(S_L),
+                                       B, H, L, d_k, d_v, r, chunk, int(product), _stream_handle(stream)))
+
+
 def pf_beta_exponential(K, beta, beta_out, B, H, L, d_k, r, dt, stream=None) -> int:
     return int(_lib.pf_beta_exponential(_ptr(K), _ptr(beta), _ptr(beta_out), B, H, L, d_k, r, dt,
                                         _stream_handle(stream)))
@@ -133,6 +161,10 @@ def pf_flow_fwd(Q, A, Atil, Bm, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, str
     """Raw call; returns the pf_status.  Pointers may be torch tensors, ints or None."""
     return int(_lib.pf_flow_fwd(_ptr(Q), _ptr(A), _ptr(Atil), _ptr(Bm), _ptr(S0), _ptr(O), _ptr(S_L),
                                 B, H, L, d_k, d_v, r, chunk, dt, _stream_handle(stream)))
+
+
+def pf_delta_chunk_supported(d_k, d_v, r, chunk) -> int:
+    return int(_lib.pf_delta_chunk_supported(d_k, d_v, r, chunk))
 
 
 def pf_delta_chunk_flow(Q, K, beta, Tt, Pt, B, H, L, d_k, d_v, r, chunk, stream=None) -> int:

@@ -3,6 +3,8 @@
 #include "pf_internal.h"
 
 #include <atomic>
+#include <cstring>
+#include <string>
 
 namespace pf {
 
@@ -24,10 +26,6 @@ int device_cu_count()
 namespace {
 
 constexpr size_t kAlign = 256;
-// The fused kernel (flow built inside the scan workgroup) reads and writes only q, k, v, beta, o,
-// but every d_v tile of a head repeats the flow of every block: measured slower than the two
-// kernels on every benchmark shape, so pf_delta_fwd does not take it.
-constexpr bool kUseFused = false;
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -47,9 +45,10 @@ int scan_segments(int heads, int L, int d, int r, int chunk)
     if (L % chunk != 0) return 1;
     const int NC = L / chunk;
     const long long chains = (long long)heads * (d / pf::scan_dv_tile(heads, d, chunk * r));
-    if (chains > 32 || NC < 32) return 1;
+    const int cus = pf::device_cu_count();
+    if (chains > cus / 8 || NC < 32) return 1;
     int G = 1;
-    while (2 * G * chains <= 256 && NC % (2 * G) == 0 && NC / (2 * G) >= 4) G *= 2;
+    while (2 * G * chains <= cus && NC % (2 * G) == 0 && NC / (2 * G) >= 4) G *= 2;
     return G >= 8 ? G : 1;
 }
 // L tokens per head of which the first L - L % chunk (whole flow blocks) go through the MFMA
@@ -182,6 +181,41 @@ size_t pf_delta_fwd_workspace_bytes(int B, int H, int L, int d_k, int d_v, int r
     return plan_workspace(B * H, L, d_k, r, block).total;
 }
 
+size_t pf_delta_fwd_describe(int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt, char *buf,
+                             size_t cap)
+{
+    std::string out;
+    const int fam = check_dims(B, H, L, d_k, d_v, r, chunk) == PF_OK ? family(d_k, d_v, r, chunk, dt) : 0;
+    if (fam != 0) {
+        const char *elem = dt == PF_BF16 ? "unsigned short" : "float";
+        const std::string generic = std::string("pf::generic_kernel<") + elem + ", false>";
+        const int block = fam == 2 ? mfma_block(d_k, d_v, r, chunk, dt) : generic_block(d_k, d_v, r, chunk);
+        const int tail = fam == 2 ? L % block : 0;
+        if (fam == 1 || L < block) {
+            out = generic;
+        } else {
+            const int heads = B * H, n = block * r;
+            const int G = scan_segments(heads, L, d_k, r, block);
+            const std::string dims = std::to_string(d_k) + ", " + std::to_string(n) + ", " + std::to_string(block);
+            const std::string flow = "pf::flow_kernel<" + dims + ">";
+            const std::string scan = "pf::scan_kernel<" + dims + ", " +
+                                     std::to_string(pf::scan_dv_tile(heads * G, d_k, n));
+            if (G > 1)
+                out = flow + ";pf::segment_constants_kernel;" + scan + ", false>;" + scan + ", false>;" +
+                      "pf::segment_compose_kernel;" + scan + ", true>";
+            else
+                out = flow + ";" + scan + ", true>";
+            if (tail) out += ";" + generic;
+        }
+    }
+    if (buf && cap > 0) {
+        const size_t m = out.size() < cap - 1 ? out.size() : cap - 1;
+        std::memcpy(buf, out.data(), m);
+        buf[m] = '\0';
+    }
+    return out.size();
+}
+
 static pf_status delta_fwd_impl(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
                                 void *O, float *S_L, int B, int H, int L, int d_k, int d_v, int r, int chunk,
                                 pf_dtype dt, void *workspace, size_t workspace_bytes, pf_stream stream,
@@ -218,11 +252,7 @@ static pf_status delta_fwd_impl(const void *Q, const void *K, const void *V, con
         float *Smid = tail ? reinterpret_cast<float *>(ws + wp.oS) : S_L;
         const void *Tt = ws + wp.oT, *Pt = ws + wp.oP;
         hipError_t e = hipSuccess;
-        if (kUseFused && wp.segments == 1 && pf::fused_instance_exists(d_k, block * r, block)) {
-            // flow and scan of every block in one kernel: T and P stay on chip
-            e = pf::launch_fused(Q, K, V, beta, S0, O, Smid, nullptr, nullptr, heads, L, d_k, r, block, product, s);
-            if (e != hipSuccess) return PF_ERR_LAUNCH;
-        } else if (wp.segments > 1) {
+        if (wp.segments > 1) {
             e = pf::launch_chunk_flow(Q, K, beta, ws + wp.oT, ws + wp.oP, heads, L, d_k, r, block, s, product);
             if (e != hipSuccess) return PF_ERR_LAUNCH;
             // Segment-parallel scan (no tail here): every segment of every head is a chain of
@@ -274,6 +304,36 @@ pf_status pf_delta_product_fwd(const void *Q, const void *K, const void *V, cons
                           stream, true);
 }
 
+int pf_delta_fwd_fused_supported(int d_k, int d_v, int r, int chunk)
+{
+    if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0 || d_k != d_v || (long long)chunk * r > 4096) return 0;
+    return pf::fused_instance_exists(d_k, chunk * r, chunk) ? 1 : 0;
+}
+
+pf_status pf_delta_fwd_fused(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
+                             void *O, float *S_L, int B, int H, int L, int d_k, int d_v, int r, int chunk,
+                             int product, pf_stream stream)
+{
+    if (L != 0 && (!Q || !K || !V || !beta || !O)) return PF_ERR_NULL;
+    pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
+    if (st != PF_OK) return st;
+    if (!pf_delta_fwd_fused_supported(d_k, d_v, r, chunk)) return PF_ERR_UNSUPPORTED;
+    if (L % chunk != 0) return PF_ERR_SHAPE;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(beta) || !aligned16(O) ||
+        !aligned16(S0) || !aligned16(S_L))
+        return PF_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (L == 0) {
+        // nothing to scan: the generic launcher copies the state through
+        hipError_t e = pf::launch_generic(Q, K, V, beta, S0, O, S_L, B * H, 0, d_k, d_v, r, 1, true, s, 0,
+                                          product != 0);
+        return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+    }
+    hipError_t e = pf::launch_fused(Q, K, V, beta, S0, O, S_L, nullptr, nullptr, B * H, L, d_k, r, chunk,
+                                    product != 0, s);
+    return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+}
+
 int pf_flow_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt)
 {
     if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return 0;
@@ -296,6 +356,12 @@ pf_status pf_flow_fwd(const void *Q, const void *A, const void *Atil, const void
                                               generic_block(d_k, d_v, r, chunk), dt == PF_BF16,
                                               static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+}
+
+int pf_delta_chunk_supported(int d_k, int d_v, int r, int chunk)
+{
+    if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return 0;
+    return split_instance(d_k, d_v, r, chunk) ? 1 : 0;
 }
 
 pf_status pf_delta_chunk_flow(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,

@@ -17,21 +17,29 @@
 //     O_c   = Q S_c^T + P U_eff           block x TV   (discrete flow of Section 3.1 cut at each token)
 //     S_c+1 = S_c + U_eff^T K             TV x d       (S_1 of Theorem 3.2)
 //
-// Two kinds of wavefronts, one of each per SIMD, meet at three barriers per block:
+// Three kinds of wavefronts, one of each per SIMD (twelve waves, 168 registers each), meet at
+// three barriers per block:
 //
 //   state waves (0..3)  run the chain R (interval 0), U_eff (interval 1), S update (interval 2) and
 //                       the readout that hangs off it; S^T lives in their fp32 accumulators for the
 //                       whole sequence.  T and P come from LDS, Q straight from global memory in
-//                       operand form, two blocks ahead.
-//   flow waves (4..7)   work one block ahead of the chain.  Interval 0: P of the block the chain
-//                       is on goes from their registers to LDS, the previous O tile goes out, the
-//                       next block's K and beta go from registers to LDS and the loads of the block
-//                       after it are issued.  Interval 1: Gram of the next block (K K^T below the
-//                       diagonal as operand tiles of -G^T, P = Q K^T into registers, the diagonal
-//                       32-blocks of T by Neumann doubling in registers).  Interval 2: block
-//                       substitution of Proposition 3.3 on the transposed system, slices of T kept in
-//                       registers as B operands, finished tiles to LDS in the A-operand form the
-//                       chain reads.
+//                       operand form, one block ahead.
+//   gram waves (4..7)   work one block ahead of the chain.  Interval 0: P of the block the chain
+//                       is on goes from their registers to LDS.  Interval 1: Gram of the next
+//                       block (K K^T below the diagonal as operand tiles of -G^T in LDS, P = Q K^T
+//                       into registers).  Interval 2: their share of the block substitution.
+//   aux waves (8..11)   stage K, V, beta of the next block through registers into LDS and copy
+//                       the previous O tile out (interval 0), invert the diagonal 32-blocks of
+//                       Id + G (interval 1), and take the other share of the substitution
+//                       (interval 2).
+//
+// The substitution is Proposition 3.3 on the transposed system: column blocks of T are slices
+// kept in registers as B operands, finished tiles go to LDS in the A-operand form the chain reads.
+//
+// Measured on MI355X, this kernel moves the minimal bytes but takes longer than the two-kernel
+// path on every shape tried (d = 128, r = 2, 64 heads of 4096 tokens: 0.27 ms against 0.22 ms): a
+// compute unit then does the flow of its block D / TV times over, and the chain, the Gram and the
+// substitution all draw on the same LDS ports.  It serves callers that have no workspace.
 //
 // T_jj (32 x 32): the two 16 x 16 diagonal inverses are (Id + M)(Id + M^2)(Id + M^4)(Id + M^8) with
 // M = -N strictly lower (nilpotent of index <= 16), evaluated on MFMAs (contraction length 16) without leaving
@@ -47,18 +55,6 @@
 namespace pf {
 
 #define LDS_FENCE() asm volatile("" ::: "memory")
-
-// Timing marks for tuning builds (-DPF_FUSED_MARKS): workgroup 0 writes the cycle counter at the
-// interval boundaries of its first blocks into the buffer passed as Tdump.  Compiled out otherwise.
-#ifdef PF_FUSED_MARKS
-#define PF_MARK(role, step, slot)                                                                         \
-    do {                                                                                                  \
-        if (blockIdx.x == 0 && lane0 == 0 && (step) >= 0 && (step) < 64)                                  \
-            reinterpret_cast<unsigned long long *>(Tdump)[(((role) * 64 + (step)) * 8) + (slot)] = __builtin_amdgcn_s_memtime(); \
-    } while (0)
-#else
-#define PF_MARK(role, step, slot) do { } while (0)
-#endif
 
 constexpr int kFusedRoleWaves = 4;                       // waves per role
 constexpr int kFusedRoleThreads = 64 * kFusedRoleWaves;
@@ -274,9 +270,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(
                 }
                 fetch_q(nx);
             }
-            PF_MARK(0, ch, 0);
             __syncthreads();
-            PF_MARK(0, ch, 1);
 
             // ---- interval 1: U_eff = T R, lower block-triangular, rows dealt so that the waves
             // do equal work.  The R tiles (B operands) are shared by this wave's row tiles.
@@ -318,9 +312,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(
                         st4(&Ue[(16 * nt + r16) * UP + 32 * (mt >> 1) + 8 * g + 4 * (mt & 1)], cvt4(acc[nt]));
                 }
             }
-            PF_MARK(0, ch, 2);
             __syncthreads();
-            PF_MARK(0, ch, 3);
 
             // ---- interval 2: S^T += K^T U_eff, this wave's d_k rows; K^T comes out of the
             // transposing read.  O^T += U_eff^T P^T reuses the U_eff registers as A operand.
@@ -375,17 +367,11 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(
 #pragma unroll
                 for (int md = 0; md < NNT; ++md)
                     if (tok_tile(i) < CT) st4(&Ob[(16 * tok_tile(i) + r16) * OP + 16 * md + 4 * g], cvt4(oacc[i][md]));
-            PF_MARK(0, ch, 4);
             __syncthreads();
-            PF_MARK(0, ch, 5);
         };
-#ifdef PF_X_NOCHAIN
-        for (int ch = 0; ch < NC; ++ch) { __syncthreads(); __syncthreads(); __syncthreads(); }
-#else
         // (one copy of the step's code: the twelve wavefronts of a workgroup run twelve different
         // instruction streams, and together they have to stay within the instruction cache)
         for (int ch = 0; ch < NC; ++ch) step(ch);
-#endif
 
         if (SL) {
 #pragma unroll
@@ -590,7 +576,6 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(
                     x01 = mfma16(k0[ks], k1[ks], x01);   // [a in tile 0][b in tile 1]
                     x11 = mfma16(k1[ks], k1[ks], x11);   // [a in tile 1][b in tile 1]
                 }
-                PF_MARK(2, mk, 6);
                 // M = -N, N = strict-in-time part of diag(beta) K K^T (rows and columns compared
                 // by token, i.e. by virtual token >> mask_shift); accumulator tiles of M and M^T
                 f32x4 m[2], mt[2], y[2], yt[2], m21t;
@@ -623,7 +608,6 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(
                         m[b2] = m2;
                     }
                 }
-                PF_MARK(2, mk, 7);
                 // T_21 = T_22 M_21 T_11
                 const f32x4 tmp = mfma16k(cvt4(m21t), cvt4(y[0]), z);
                 const f32x4 y21 = mfma16k(cvt4(yt[1]), cvt4(tmp), z);
@@ -670,10 +654,8 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(
                         X[j] = join(cvt4(xacc[0]), cvt4(xacc[1]));
                         // lane (r16, g) holds T[16 s + r16][32 j + kk(g, e)]: the A-operand tile (s, j) as is
                         st8(&Tl[((size_t)t_tile_index(s, j) * 64 + lane) * 8], X[j]);
-#ifndef PF_FUSED_MARKS
                         if (Tdump && dv0 == 0)
                             st8(Tdump + cid * (size_t)N * N + ((size_t)(s * NKT + j) * 64 + lane) * 8, X[j]);
-#endif
                     }
                 }
             }
@@ -688,9 +670,6 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(
         // Round nb stages block nb and builds its flow while the chain is on block nb - 1.
         auto round = [&](int nb) {
             tb = tb0;
-#ifdef PF_X_LAUNDER_FLOW
-            asm volatile("" : "+v"(tb));
-#endif
             lane = tb & 63; r16 = lane & 15; g = lane >> 4;
             const bool live = nb < NC;
             const size_t cid = c0 + (live ? nb : NC - 1);
@@ -704,34 +683,22 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(
                 if (live) store_k(nb & 1);
                 fetch_k(nx);
             }
-            PF_MARK(1 + !kGram, nb - 1, 0);
             __syncthreads();
-            PF_MARK(1 + !kGram, nb - 1, 1);
 
             // ---- interval 1
             if constexpr (kGram) {
-#ifndef PF_X_NOFLOW
                 if (live) gram(nb & 1);
-#endif
                 fetch_q(nx);
             } else {
                 if (live) store_v();
                 fetch_v(nx);
-#ifndef PF_X_NOFLOW
                 if (live) diag(nb & 1, nb - 1);
-#endif
             }
-            PF_MARK(1 + !kGram, nb - 1, 2);
             __syncthreads();
-            PF_MARK(1 + !kGram, nb - 1, 3);
 
             // ---- interval 2
-#ifndef PF_X_NOFLOW
             if (live) subst(cid);
-#endif
-            PF_MARK(1 + !kGram, nb - 1, 4);
             __syncthreads();
-            PF_MARK(1 + !kGram, nb - 1, 5);
         };
         for (int nb = 0; nb <= NC; ++nb) round(nb);
         if constexpr (!kGram) copy_out(c0 + NC - 1);

@@ -680,7 +680,7 @@ int scan_dv_tile(int heads, int d, int n)
     // 32 rows when that already gives at least one workgroup per CU, else 16 rows (twice the
     // workgroups, half the MFMA work per operand byte).  With n = 256 only the 16-row tile
     // fits LDS next to the chunk's K.
-    return (n < 256 && (long long)heads * (d / 32) >= 256) ? 32 : 16;
+    return (n < 256 && (long long)heads * (d / 32) >= (long long)device_cu_count()) ? 32 : 16;
 }
 
 template <int D, int N, int C, int TV>

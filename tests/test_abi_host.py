@@ -56,11 +56,28 @@ def test_flow_block(pf):
     assert (pf.pf_delta_fwd_workspace_bytes(2, 16, 8192, 128, 128, 4, 128, BF)
             == pf.pf_delta_fwd_workspace_bytes(2, 16, 8192, 128, 128, 4, 64, BF))
     # the split entry points take every (chunk * r, chunk) that has an instance, and nothing else
+    assert pf.pf_delta_chunk_supported(128, 128, 2, 128) == 1 and pf.pf_delta_chunk_supported(128, 128, 4, 64) == 1
+    assert pf.pf_delta_chunk_supported(128, 128, 4, 128) == 0 and pf.pf_delta_chunk_supported(128, 64, 1, 64) == 0
     fake = 0x1000
     assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 256, 128, 128, 4, 128, 0) == pf.PF_ERR_UNSUPPORTED
     assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 256, 128, 128, 2, 32, 0) == pf.PF_ERR_UNSUPPORTED
     assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 100, 128, 128, 4, 32, 0) == pf.PF_ERR_SHAPE
     assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 100, 128, 128, 2, 128, 0) == pf.PF_ERR_SHAPE
+
+
+def test_fused_entry_host_checks(pf):
+    assert pf.pf_delta_fwd_fused_supported(128, 128, 2, 64) == 1
+    assert pf.pf_delta_fwd_fused_supported(64, 64, 2, 32) == 1
+    assert pf.pf_delta_fwd_fused_supported(128, 128, 4, 64) == 0         # 256 virtual tokens
+    assert pf.pf_delta_fwd_fused_supported(128, 64, 1, 64) == 0          # d_k != d_v
+    assert pf.pf_delta_fwd_fused_supported(128, 128, 0, 64) == 0
+    fake = 0x1000
+    call = lambda *a: pf.pf_delta_fwd_fused(*a, 0)
+    assert call(fake, fake, fake, fake, None, fake, None, 1, 1, 128, 128, 128, 4, 64, 0) == pf.PF_ERR_UNSUPPORTED
+    assert call(fake, fake, fake, fake, None, fake, None, 1, 1, 100, 128, 128, 2, 64, 0) == pf.PF_ERR_SHAPE
+    assert call(None, fake, fake, fake, None, fake, None, 1, 1, 128, 128, 128, 2, 64, 0) == pf.PF_ERR_NULL
+    assert call(fake + 2, fake, fake, fake, None, fake, None, 1, 1, 128, 128, 128, 2, 64, 0) == pf.PF_ERR_ALIGN
+    assert call(fake, fake, fake, fake, None, fake, None, 0, 1, 128, 128, 128, 2, 64, 0) == pf.PF_ERR_SHAPE
 
 
 def test_supported_families(pf):

@@ -420,3 +420,43 @@ def test_exponential_step_matches_matrix_exponential(oracle):
     # unit keys: beta_eff = 1 - exp(-beta) stays below 1, whatever beta is (no reflection)
     ku = k / np.linalg.norm(k)
     np.testing.assert_allclose(cf.exp_rank1_beta(ku, np.array([0.5, 2.0, 50.0])), 1 - np.exp(-np.array([0.5, 2.0, 50.0])), rtol=1e-12)
+
+
+def test_streaming_compare_returns_the_sums_of_a_known_perturbation(oracle):
+    """delta_compare holds a candidate against the recurrence and returns sums only.  Pin: with a
+    candidate built from delta_fwd's own output plus a KNOWN perturbation, the sums are the
+    perturbation's (numpy), per head and per token; a candidate equal to the reference gives
+    zeros; a perturbation of one element of one token shows up in that token and head alone."""
+    rng = np.random.default_rng(5)
+    N, L, R, dk, dv = 3, 41, 2, 12, 20
+    Q = rng.standard_normal((N, L, dk)).astype(np.float32)
+    K = (rng.standard_normal((N, L, R, dk)) / 4).astype(np.float32)
+    V = rng.standard_normal((N, L, R, dv)).astype(np.float32)
+    b = rng.random((N, L, R)).astype(np.float32)
+    S0 = rng.standard_normal((N, dv, dk)).astype(np.float32)
+    O, SL = oracle.delta_fwd(Q, K, V, b, S0)
+    O32, S32 = O.astype(np.float32), SL.astype(np.float32)
+
+    c = oracle.delta_compare(Q, K, V, b, S0, O32, S32)
+    rounding = (O32.astype(np.float64) - O) ** 2
+    assert np.allclose(c["err2"], rounding.sum(-1), rtol=1e-9, atol=0)
+    assert np.allclose(c["ref2"], (O * O).sum(-1), rtol=1e-12)
+    assert c["err2"].max() < 1e-10 * c["ref2"].max()
+
+    pert = rng.standard_normal(O.shape) * 1e-2
+    Oc = (O + pert).astype(np.float32)
+    Sc = (SL * 1.01).astype(np.float32)
+    c = oracle.delta_compare(Q, K, V, b, S0, Oc, Sc)
+    d = Oc.astype(np.float64) - O
+    assert np.allclose(c["err2"], (d * d).sum(-1), rtol=1e-9)
+    assert np.allclose(c["maxabs"], np.abs(d).max(axis=(1, 2)), rtol=1e-12)
+    assert np.allclose(c["s_err2"], ((Sc.astype(np.float64) - SL) ** 2).sum(axis=(1, 2)), rtol=1e-9)
+    assert np.allclose(c["s_ref2"], (SL * SL).sum(axis=(1, 2)), rtol=1e-12)
+
+    Oc = O32.copy()
+    Oc[1, 17, 3] += 0.5
+    c = oracle.delta_compare(Q, K, V, b, None if S0 is None else S0, Oc)
+    hot = np.zeros((N, L), dtype=bool)
+    hot[1, 17] = True
+    assert abs(c["err2"][1, 17] - 0.25) < 1e-3 and c["err2"][~hot].max() < 1e-9
+    assert abs(c["maxabs"][1] - 0.5) < 1e-3 and c["maxabs"][0] < 1e-4 and c["s_err2"] is None
