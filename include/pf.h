@@ -44,7 +44,8 @@ typedef enum {
     PF_ERR_UNSUPPORTED = 3, /* no kernel instance for this (d_k, d_v, r, chunk, dt) */
     PF_ERR_ALIGN = 4,       /* a base address is not 16-byte aligned */
     PF_ERR_WORKSPACE = 5,   /* workspace is NULL or smaller than pf_delta_fwd_workspace_bytes() */
-    PF_ERR_LAUNCH = 6       /* the HIP runtime refused a launch */
+    PF_ERR_LAUNCH = 6,      /* the HIP runtime refused a launch */
+    PF_ERR_SCRATCH_LIMIT = 7 /* pf_delta_fwd_static: the call needs more than pf_delta_fwd_static_limit() bytes */
 } pf_status;
 
 typedef enum { PF_F32 = 0, PF_BF16 = 1 } pf_dtype;
@@ -131,6 +132,34 @@ pf_status pf_delta_fwd(const void *Q, const void *K, const void *V, const void *
                        const float *S0, void *O, float *S_L,
                        int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt,
                        void *workspace, size_t workspace_bytes, pf_stream stream);
+
+/*
+ * pf_delta_fwd for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and error behaviour as pf_delta_fwd without the workspace pair; the scratch
+ * the kernels need (T and P of every flow block, the per-segment matrices of the segment-parallel
+ * scan, the state handed to the tail) lives in a buffer of pf_delta_fwd_static_limit() bytes
+ * (32 MiB) inside the library's code object, one copy per GPU, held until the process ends.
+ * The call allocates nothing, frees nothing and calls no allocating routine.
+ *
+ *   - A call whose pf_delta_fwd_workspace_bytes(...) exceeds the limit returns
+ *     PF_ERR_SCRATCH_LIMIT and does nothing (d = 128, r = 2, chunk 64 needs 48 KiB per block
+ *     of 64 tokens, so about B * H * L = 43 000 token-heads fit; d = 64, r = 1: 16 KiB per block).
+ *   - Every call on a GPU shares that GPU's buffer: calls that may overlap in time on one GPU
+ *     (different streams, different host threads) race; order them on one stream.  Nothing in
+ *     the buffer has to start at zero, so nothing is cleared between calls.
+ *   - The buffer's device address is looked up at the first call on each device (or by
+ *     pf_init); make that first call, or pf_init(), outside graph capture.
+ *
+ * pf_init(): optional set-up for the current device (looks up the static buffer, asks the
+ * compute-unit count); PF_OK or PF_ERR_LAUNCH.  pf_delta_fwd_static_limit(): host only.
+ */
+pf_status pf_init(void);
+size_t pf_delta_fwd_static_limit(void);
+pf_status pf_delta_fwd_static(const void *Q, const void *K, const void *V, const void *beta,
+                              const float *S0, void *O, float *S_L,
+                              int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt,
+                              pf_stream stream);
 
 /*
  * Product form of the rank-r transition (the DeltaProduct-style reading that Section 1 cites, as

@@ -10,11 +10,12 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpf.so")
 
-PF_OK, PF_ERR_NULL, PF_ERR_SHAPE, PF_ERR_UNSUPPORTED, PF_ERR_ALIGN, PF_ERR_WORKSPACE, PF_ERR_LAUNCH = range(7)
+(PF_OK, PF_ERR_NULL, PF_ERR_SHAPE, PF_ERR_UNSUPPORTED, PF_ERR_ALIGN, PF_ERR_WORKSPACE, PF_ERR_LAUNCH,
+ PF_ERR_SCRATCH_LIMIT) = range(8)
 PF_F32, PF_BF16 = 0, 1
 
 EXPORTS = ["pf_version", "pf_status_str", "pf_delta_fwd_supported", "pf_delta_fwd_block", "pf_delta_fwd_workspace_bytes",
-           "pf_delta_fwd_describe", "pf_delta_fwd", "pf_delta_product_fwd", "pf_delta_fwd_fused_supported", "pf_delta_fwd_fused", "pf_beta_exponential", "pf_flow_fwd_supported", "pf_flow_fwd", "pf_delta_chunk_supported", "pf_delta_chunk_flow", "pf_delta_chunk_scan",
+           "pf_delta_fwd_describe", "pf_delta_fwd", "pf_init", "pf_delta_fwd_static_limit", "pf_delta_fwd_static", "pf_delta_product_fwd", "pf_delta_fwd_fused_supported", "pf_delta_fwd_fused", "pf_beta_exponential", "pf_flow_fwd_supported", "pf_flow_fwd", "pf_delta_chunk_supported", "pf_delta_chunk_flow", "pf_delta_chunk_scan",
            "pf_delta_chunk_sigdelta_supported", "pf_delta_chunk_sigdelta_workspace_bytes", "pf_delta_chunk_sigdelta"]
 
 
@@ -44,6 +45,12 @@ def _load() -> ctypes.CDLL:
     lib.pf_delta_fwd_describe.argtypes = [i] * 8 + [ctypes.c_char_p, sz]
     lib.pf_delta_fwd.restype = i
     lib.pf_delta_fwd.argtypes = [vp] * 7 + [i] * 8 + [vp, sz, vp]
+    lib.pf_init.restype = i
+    lib.pf_init.argtypes = []
+    lib.pf_delta_fwd_static_limit.restype = sz
+    lib.pf_delta_fwd_static_limit.argtypes = []
+    lib.pf_delta_fwd_static.restype = i
+    lib.pf_delta_fwd_static.argtypes = [vp] * 7 + [i] * 8 + [vp]
     lib.pf_delta_product_fwd.restype = i
     lib.pf_delta_product_fwd.argtypes = [vp] * 7 + [i] * 8 + [vp, sz, vp]
     lib.pf_delta_fwd_fused_supported.restype = i
@@ -128,6 +135,20 @@ def pf_delta_fwd(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, wor
     return int(_lib.pf_delta_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(beta), _ptr(S0), _ptr(O), _ptr(S_L),
                                  B, H, L, d_k, d_v, r, chunk, dt, _ptr(workspace), workspace_bytes,
                                  _stream_handle(stream)))
+
+
+def pf_init() -> int:
+    return int(_lib.pf_init())
+
+
+def pf_delta_fwd_static_limit() -> int:
+    return int(_lib.pf_delta_fwd_static_limit())
+
+
+def pf_delta_fwd_static(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, stream=None) -> int:
+    """Raw call (no workspace argument, nothing allocated); returns the pf_status."""
+    return int(_lib.pf_delta_fwd_static(_ptr(Q), _ptr(K), _ptr(V), _ptr(beta), _ptr(S0), _ptr(O), _ptr(S_L),
+                                        B, H, L, d_k, d_v, r, chunk, dt, _stream_handle(stream)))
 
 
 def pf_delta_product_fwd(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, workspace, workspace_bytes,

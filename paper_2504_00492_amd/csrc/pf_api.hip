@@ -139,6 +139,32 @@ pf_status check_dims(int B, int H, int L, int d_k, int d_v, int r, int chunk)
     return PF_OK;
 }
 
+// ---- scratch of pf_delta_fwd_static: a buffer inside the loaded code object, so that the entry
+// point needs no allocation and no workspace argument.  In host code the array's name is only a
+// stand-in for the symbol; its device address is asked once per device (each GPU holds its own
+// copy at its own address) and only that pointer is ever passed on.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+hipError_t static_scratch(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<void *> cached[kMaxDevices];
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void *p = cached[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        cached[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -155,6 +181,7 @@ const char *pf_status_str(pf_status s)
     case PF_ERR_ALIGN: return "a base address is not 16-byte aligned";
     case PF_ERR_WORKSPACE: return "workspace is NULL or too small";
     case PF_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+    case PF_ERR_SCRATCH_LIMIT: return "the call needs more scratch than the library's static buffer holds";
     }
     return "unknown status";
 }
@@ -302,6 +329,36 @@ pf_status pf_delta_product_fwd(const void *Q, const void *K, const void *V, cons
 {
     return delta_fwd_impl(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, workspace, workspace_bytes,
                           stream, true);
+}
+
+pf_status pf_init(void)
+{
+    void *p = nullptr;
+    if (static_scratch(&p) != hipSuccess) return PF_ERR_LAUNCH;
+    (void)pf::device_cu_count();
+    return PF_OK;
+}
+
+size_t pf_delta_fwd_static_limit(void) { return kStaticScratchBytes; }
+
+pf_status pf_delta_fwd_static(const void *Q, const void *K, const void *V, const void *beta, const float *S0,
+                              void *O, float *S_L, int B, int H, int L, int d_k, int d_v, int r, int chunk,
+                              pf_dtype dt, pf_stream stream)
+{
+    // every check that needs no device first, so that a bad call has no effect at all
+    if (L != 0 && (!Q || !K || !V || !beta || !O)) return PF_ERR_NULL;
+    pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
+    if (st != PF_OK) return st;
+    if (family(d_k, d_v, r, chunk, dt) == 0) return PF_ERR_UNSUPPORTED;
+    const size_t need = pf_delta_fwd_workspace_bytes(B, H, L, d_k, d_v, r, chunk, dt);
+    if (need > kStaticScratchBytes) return PF_ERR_SCRATCH_LIMIT;
+    void *ws = nullptr;
+    if (need > 0 && static_scratch(&ws) != hipSuccess) return PF_ERR_LAUNCH;
+    // Nothing in the scratch has to start at zero: every tile of T and P that the scan kernel
+    // reads is written by the flow kernel of the same call, and the segment-parallel path
+    // writes its constants itself.  What an earlier call left behind is simply overwritten.
+    return delta_fwd_impl(Q, K, V, beta, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, ws, need ? kStaticScratchBytes : 0,
+                          stream, false);
 }
 
 int pf_delta_fwd_fused_supported(int d_k, int d_v, int r, int chunk)

@@ -36,8 +36,8 @@ def test_header_symbols_are_exported(pf):
 
 def test_version_and_status_strings(pf):
     assert pf.pf_version() >= 100
-    seen = {pf.pf_status_str(s) for s in range(7)}
-    assert len(seen) == 7 and all(seen)
+    seen = {pf.pf_status_str(s) for s in range(8)}
+    assert len(seen) == 8 and all(seen)
     assert pf.pf_status_str(99) == "unknown status"
 
 
