@@ -1,7 +1,7 @@
 // Fused forward: steps 2 and 3 of Section 3 of ParallelFlow (arXiv 2504.00492) in one kernel.
 // The flow of a block (Theorem 3.2) is built inside the workgroup that scans the block, so the
 // compact form T and the masked readout matrix P never leave the compute unit: HBM sees q, k, v,
-// beta once and o once.
+// beta once and o once, as long as the d_v tiles of a head stay in step (see below).
 //
 // Rows of S evolve independently (the recurrence of Section 3.1 multiplies S from the right), so a
 // workgroup owns TV rows of S (a tile of d_v) of one (b, h) and walks the blocks.  The d_v tiles of
@@ -36,10 +36,13 @@
 // The substitution is Proposition 3.3 on the transposed system: column blocks of T are slices
 // kept in registers as B operands, finished tiles go to LDS in the A-operand form the chain reads.
 //
-// Measured on MI355X, this kernel moves the minimal bytes but takes longer than the two-kernel
-// path on every shape tried (d = 128, r = 2, 64 heads of 4096 tokens: 0.27 ms against 0.22 ms): a
-// compute unit then does the flow of its block D / TV times over, and the chain, the Gram and the
-// substitution all draw on the same LDS ports.  It serves callers that have no workspace.
+// Measured on MI355X (d = 128, r = 2): 64 heads of 4096 tokens, 32-row tiles: 1.01 times the
+// minimal HBM bytes, 0.22 ms, the same time as the two-kernel path; 32 heads of 65536 tokens,
+// 16-row tiles: 1.76 times the minimal bytes (the eight tiles of a head drift apart over 1024
+// blocks and miss each other's K and Q in L2), 2.8 ms against 2.4 ms.  A compute unit does the
+// flow of its block D / TV times over, and the chain, the Gram and the substitution all draw on
+// the same LDS ports (MFMA pipe busy 31 %, LDS 56 % of the cycles).  It serves callers that
+// have no workspace.
 //
 // T_jj (32 x 32): the two 16 x 16 diagonal inverses are (Id + M)(Id + M^2)(Id + M^4)(Id + M^8) with
 // M = -N strictly lower (nilpotent of index <= 16), evaluated on MFMAs (contraction length 16) without leaving
