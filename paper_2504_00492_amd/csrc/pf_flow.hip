@@ -321,7 +321,7 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
                     X[sl][j] = join(cvt4(xacc[0]), cvt4(xacc[1]));
                     // lane (r16, g) now holds T[16 s + r16][32 j + 4 g + e] (e < 4) and
                     // T[16 s + r16][32 j + 16 + 4 g + e - 4] (e >= 4): the A-operand tile (s, j) as is.
-                    st8(Ttg + ((size_t)(s * NKT + j) * 64 + lane) * 8, X[sl][j]);
+                    st8(Ttg + full_tile_offset(NKT, s, j) + lane * 8, X[sl][j]);
                 }
             }
             __syncthreads();
@@ -353,7 +353,7 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
                 if ((32 * kt + 4 * g + jj) / R > t) acc0[jj] = 0.0f;
                 if ((32 * kt + 16 + 4 * g + jj) / R > t) acc1[jj] = 0.0f;
             }
-            st8(Ptg + ((size_t)(tt * NKT + kt) * 64 + lane) * 8, join(cvt4(acc0), cvt4(acc1)));
+            st8(Ptg + full_tile_offset(NKT, tt, kt) + lane * 8, join(cvt4(acc0), cvt4(acc1)));
         }
         __syncthreads();   // every read of this chunk's K, Q is done before the next chunk lands
     }
@@ -382,17 +382,9 @@ static hipError_t launch_flow_instance(const void *Q, const void *K, const void 
         while ((1 << mask_shift) < N / C) ++mask_shift;
     constexpr size_t lds = FlowLds<D, N, C>::total;
     static_assert(lds <= kMaxLdsBytes, "flow kernel LDS plan exceeds the CU");
-    // the LDS opt-in is per device and sticks: ask once per device, not once per launch
-    static std::atomic<int> armed_device{-1};
-    int dev = -1;
-    hipError_t e = hipGetDevice(&dev);
+    static std::atomic<uint64_t> armed{0};
+    hipError_t e = arm_dynamic_lds(armed, reinterpret_cast<const void *>(kern), lds);
     if (e != hipSuccess) return e;
-    if (armed_device != dev) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        armed_device = dev;
-    }
     // Persistent grid: as many workgroups as the chip holds at once (LDS decides how many per
     // CU, at most two), each walking its share of the chunks.
     const size_t per_cu = kMaxLdsBytes / lds ? kMaxLdsBytes / lds : 1;

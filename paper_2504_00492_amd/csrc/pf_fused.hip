@@ -490,7 +490,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(
                     if (kt < p_ksteps(R, tt)) {
                         st8(&Pl[((size_t)p_tile_index(R, tt, kt) * 64 + lane) * 8], pP[i][kt]);
                         if (Pdump && dv0 == 0)
-                            st8(Pdump + cid * (size_t)C * N + ((size_t)(tt * NKT + kt) * 64 + lane) * 8, pP[i][kt]);
+                            st8(Pdump + cid * (size_t)C * N + full_tile_offset(NKT, tt, kt) + lane * 8, pP[i][kt]);
                     }
             }
         };
@@ -658,7 +658,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_kernel(
                         // lane (r16, g) holds T[16 s + r16][32 j + kk(g, e)]: the A-operand tile (s, j) as is
                         st8(&Tl[((size_t)t_tile_index(s, j) * 64 + lane) * 8], X[j]);
                         if (Tdump && dv0 == 0)
-                            st8(Tdump + cid * (size_t)N * N + ((size_t)(s * NKT + j) * 64 + lane) * 8, X[j]);
+                            st8(Tdump + cid * (size_t)N * N + full_tile_offset(NKT, s, j) + lane * 8, X[j]);
                     }
                 }
             }
@@ -752,17 +752,9 @@ static hipError_t launch_fused_tv(const void *Q, const void *K, const void *V, c
     int mask_shift = 0;
     if (!product)
         while ((1 << mask_shift) < N / C) ++mask_shift;
-    // the LDS opt-in is per device and sticks: ask once per device, not once per launch
-    static std::atomic<int> armed_device{-1};
-    int dev = -1;
-    hipError_t e = hipGetDevice(&dev);
+    static std::atomic<uint64_t> armed{0};
+    hipError_t e = arm_dynamic_lds(armed, reinterpret_cast<const void *>(kern), lds);
     if (e != hipSuccess) return e;
-    if (armed_device != dev) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        armed_device = dev;
-    }
     const unsigned grid = (unsigned)heads * (D / TV);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kFusedThreads), lds, stream, (const bf16 *)Q, (const bf16 *)K,
                        (const bf16 *)V, (const bf16 *)beta, S0, (bf16 *)O, SL, (bf16 *)Tdump, (bf16 *)Pdump,

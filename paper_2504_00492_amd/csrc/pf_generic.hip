@@ -188,8 +188,9 @@ static hipError_t launch_generic_instance(const void *Q, const void *K, const vo
 {
     const size_t lds = generic_lds_bytes(dk, dv, r, chunk);
     auto kern = generic_kernel<T, kDrivers>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    // the opt-in is for the largest size any call may ask for, so that it is made once per device
+    static std::atomic<uint64_t> armed{0};
+    hipError_t e = arm_dynamic_lds(armed, reinterpret_cast<const void *>(kern), kMaxLdsBytes);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(heads), dim3(256), lds, stream, (const T *)Q, (const T *)K, (const T *)V,
                        (const T *)beta, S0, (T *)O, SL, L, dk, dv, r, chunk, t0, product ? 1 : r);

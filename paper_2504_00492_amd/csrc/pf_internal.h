@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace pf {
 
 constexpr size_t kMaxLdsBytes = 160 * 1024;  // LDS per workgroup (and per CU) on gfx950
@@ -12,6 +14,21 @@ constexpr size_t kMaxLdsBytes = 160 * 1024;  // LDS per workgroup (and per CU) o
 // Compute units of the current device (asked once per device, then cached); 256, the count of
 // an MI355X, when no device answers (host-only callers).
 int device_cu_count();
+
+// Opt a kernel in to `bytes` of dynamic LDS.  The attribute belongs to (kernel, device) and
+// sticks, so it is set once per device: `armed` (one per kernel instantiation, zero-initialised)
+// keeps a bit per device ordinal.
+inline hipError_t arm_dynamic_lds(std::atomic<uint64_t> &armed, const void *kernel, size_t bytes)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t)1 << dev : 0;
+    if (bit && (armed.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && bit) armed.fetch_or(bit, std::memory_order_release);
+    return e;
+}
 
 // ---- generic path (pf_generic.hip)
 size_t generic_lds_bytes(int dk, int dv, int r, int chunk);

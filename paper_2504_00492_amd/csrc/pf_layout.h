@@ -25,6 +25,10 @@
 
 namespace pf {
 
+// Global memory, full grids: element offset of tile (rt, kt) inside its block's array, NKT
+// k-steps per row of tiles (rt = mt for T, tt for P); lane l's eight elements follow at 8 l.
+constexpr size_t full_tile_offset(int NKT, int rt, int kt) { return ((size_t)rt * NKT + kt) * 64 * 8; }
+
 // T: row tile mt has mt / 2 + 1 tiles
 constexpr int t_tile_index(int mt, int kt)
 {

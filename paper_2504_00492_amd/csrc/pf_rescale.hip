@@ -3,7 +3,7 @@
 // (Section 3.3 of ParallelFlow, arXiv 2504.00492: exp(a b^T) = Id + ((e^x - 1) / x) a b^T with
 // x = <b, a>, here a = beta k, b = -k; the input increment picks up the same factor).
 // One row of K per 16 lanes: 16-byte loads where the row length allows, partial sums combined
-// with DPP shuffles inside the 16-lane row, fp32 arithmetic.
+// with cross-lane shuffles (__shfl_xor) inside the 16-lane row, fp32 arithmetic.
 #include "pf_internal.h"
 #include "pf_common.h"
 

@@ -179,7 +179,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 const int tt = tok_tile(i);
 #pragma unroll
                 for (int kt = 0; kt < NKT; ++kt)
-                    if (kt < ksteps_of(tt)) p2[S][i][kt] = ld8(Pc + ((size_t)(tt * NKT + kt) * 64 + lane) * 8);
+                    if (kt < ksteps_of(tt)) p2[S][i][kt] = ld8(Pc + full_tile_offset(NKT, tt, kt) + lane * 8);
             }
         };
 
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 const int mt = row_tile(i);
 #pragma unroll
                 for (int kt = 0; kt < NKT; ++kt)
-                    if (2 * kt <= mt) t1[S][i][kt] = ld8(Tc + ((size_t)(mt * NKT + kt) * 64 + lane) * 8);
+                    if (2 * kt <= mt) t1[S][i][kt] = ld8(Tc + full_tile_offset(NKT, mt, kt) + lane * 8);
             }
         };
         constexpr std::integral_constant<int, 0> kSet0{};
@@ -469,7 +469,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 const int tt = tok_tile(i);
 #pragma unroll
                 for (int kt = 0; kt < NKT; ++kt)
-                    if (kt < ksteps_of(tt)) p2[S][i][kt] = ld8(Pc + ((size_t)(tt * NKT + kt) * 64 + lane) * 8);
+                    if (kt < ksteps_of(tt)) p2[S][i][kt] = ld8(Pc + full_tile_offset(NKT, tt, kt) + lane * 8);
             }
         };
         // Q of this wave's token tiles, straight from global memory in B-operand form
@@ -657,17 +657,9 @@ static hipError_t launch_scan_ro(const void *Q, const void *K, const void *V, co
     auto kern = scan_kernel<D, N, C, TV, RO>;
     constexpr size_t lds = ScanLds<D, N, C, TV>::total;
     static_assert(lds <= kMaxLdsBytes, "scan kernel LDS plan exceeds the CU");
-    // the LDS opt-in is per device and sticks: ask once per device, not once per launch
-    static std::atomic<int> armed_device{-1};
-    int dev = -1;
-    hipError_t e = hipGetDevice(&dev);
+    static std::atomic<uint64_t> armed{0};
+    hipError_t e = arm_dynamic_lds(armed, reinterpret_cast<const void *>(kern), lds);
     if (e != hipSuccess) return e;
-    if (armed_device != dev) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        armed_device = dev;
-    }
     const unsigned grid = (unsigned)heads * (D / TV);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kScanThreads), lds, stream, (const bf16 *)Q,
                        (const bf16 *)K, (const bf16 *)V, (const bf16 *)beta, (const bf16 *)Tt,

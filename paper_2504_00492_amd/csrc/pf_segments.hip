@@ -36,7 +36,7 @@ hipError_t launch_segment_constants(void *zeroV, float *ident, int n, int d, hip
 // x = tid, tid + 256, ... of every row.
 constexpr int kComposeRows = 8;
 
-__global__ __launch_bounds__(256) void segment_compose_kernel(const float *__restrict__ S0,
+__global__ __launch_bounds__(256) void segment_compose_kernel(const float *S0,
                                                               const float *__restrict__ Pseg,
                                                               const float *__restrict__ Hseg,
                                                               float *__restrict__ Sin, float *SL, int G, int d)

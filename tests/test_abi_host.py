@@ -65,6 +65,39 @@ def test_flow_block(pf):
     assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 100, 128, 128, 2, 128, 0) == pf.PF_ERR_SHAPE
 
 
+def test_describe_names_the_kernels_a_call_launches(pf):
+    BF, F32 = pf.PF_BF16, pf.PF_F32
+    # (the d_v tile depends on the compute-unit count: 256 is assumed when no device answers)
+    assert pf.pf_delta_fwd_describe(4, 16, 4096, 128, 128, 2, 64, BF) == [
+        "pf::flow_kernel<128, 128, 64>", "pf::scan_kernel<128, 128, 64, 32, true>"]
+    assert pf.pf_delta_fwd_describe(1, 32, 65536, 128, 128, 2, 128, BF) == [           # chunk 128 -> blocks of 64
+        "pf::flow_kernel<128, 128, 64>", "pf::scan_kernel<128, 128, 64, 16, true>"]
+    seg = pf.pf_delta_fwd_describe(1, 4, 65536, 128, 128, 2, 64, BF)                    # few heads: segments
+    assert seg[0] == "pf::flow_kernel<128, 128, 64>" and seg[-1] == "pf::scan_kernel<128, 128, 64, 16, true>"
+    assert seg.count("pf::scan_kernel<128, 128, 64, 16, false>") == 2 and "pf::segment_compose_kernel" in seg
+    assert pf.pf_delta_fwd_describe(1, 4, 100, 128, 128, 2, 64, BF)[-1] == "pf::generic_kernel<unsigned short, false>"
+    assert pf.pf_delta_fwd_describe(1, 1, 64, 16, 16, 1, 16, F32) == ["pf::generic_kernel<float, false>"]
+    assert pf.pf_delta_fwd_describe(1, 1, 64, 256, 256, 1, 16, F32) == []               # unsupported
+    assert pf.pf_delta_fwd_describe(0, 1, 64, 16, 16, 1, 16, F32) == []                 # invalid
+    # a short buffer gets a truncated, terminated string and the full length comes back
+    import ctypes
+    from paper_2504_00492_amd.binding import _lib
+    buf = ctypes.create_string_buffer(8)
+    n = _lib.pf_delta_fwd_describe(4, 16, 4096, 128, 128, 2, 64, BF, buf, 8)
+    assert n == len("pf::flow_kernel<128, 128, 64>;pf::scan_kernel<128, 128, 64, 32, true>") and buf.value == b"pf::flo"
+
+
+def test_static_entry_host_checks(pf):
+    assert pf.pf_delta_fwd_static_limit() == 32 << 20
+    fake = 0x1000
+    BF = pf.PF_BF16
+    args = (fake, fake, fake, fake, None, fake, None)
+    assert pf.pf_delta_fwd_static(*args, 4, 16, 4096, 128, 128, 2, 64, BF, 0) == pf.PF_ERR_SCRATCH_LIMIT
+    assert pf.pf_delta_fwd_static(None, fake, fake, fake, None, fake, None, 1, 1, 64, 128, 128, 2, 64, BF, 0) == pf.PF_ERR_NULL
+    assert pf.pf_delta_fwd_static(*args, 1, 1, 64, 256, 256, 1, 8, pf.PF_F32, 0) == pf.PF_ERR_UNSUPPORTED
+    assert pf.pf_delta_fwd_static(*args, 1, 0, 64, 128, 128, 2, 64, BF, 0) == pf.PF_ERR_SHAPE
+
+
 def test_fused_entry_host_checks(pf):
     assert pf.pf_delta_fwd_fused_supported(128, 128, 2, 64) == 1
     assert pf.pf_delta_fwd_fused_supported(64, 64, 2, 32) == 1
