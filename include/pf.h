@@ -66,12 +66,13 @@ const char *pf_status_str(pf_status s);
  *      dtypes, any d_k, d_v, r; the chunk is halved until its working set fits 160 KiB of LDS next
  *      to the fp32 state (unsupported only when not even one token does); L need not be a
  *      multiple of chunk (the tail is a shorter last chunk)
- *   2  MFMA path (PF_BF16 only): d_k = d_v in {64, 128} and a flow block (see
+ *   2  MFMA path (PF_BF16 only): d_k in {64, 128}, d_v any multiple of 16 (the state is split into
+ *      tiles of 16 or 32 rows of d_v, so d_v need not equal d_k), and a flow block (see
  *      pf_delta_fwd_block) with block * r in {64, 128, 256}, block in {32, 64, 128}.  Any L: the
  *      L % block tokens left over at the end of every (b, h) are taken by the generic kernel
  *      from the state the whole blocks leave behind (the flows compose, Section 3.1).
  *      With few (b, h) pairs and a long L (the plain scan would use at most an eighth of the
- *      GPU) every head is cut into 8 or more segments that are scanned side by side: a
+ *      GPU) and d_k = d_v, every head is cut into 8 or more segments that are scanned side by side: a
  *      segment acts on the state as S -> S P + H (Proposition 2.1), P and H of all segments are
  *      computed in parallel, composed per head, and the segments re-run from their true
  *      incoming states.  Same results up to rounding; the workspace grows by a few d x d
@@ -228,10 +229,11 @@ pf_status pf_flow_fwd(const void *Q, const void *A, const void *Atil, const void
 
 /*
  * Step 2 of Section 3 on its own ("parallel compute": the flow of every chunk, no dependence
- * between chunks), MFMA path only: d_k = d_v in {64, 128} and (chunk * r, chunk) one of (64, 64),
- * (128, 32), (128, 64), (128, 128), (256, 64), (256, 128), else PF_ERR_UNSUPPORTED; L a multiple of
- * chunk, else PF_ERR_SHAPE.  With n = chunk * r,
- * d = d_k = d_v and NC = L / chunk, for every (b, h, c):
+ * between chunks), MFMA path only: d_k in {64, 128}, d_v a multiple of 16 (the flow does not depend on
+ * d_v; the argument is checked so that both split entry points accept the same dimensions) and
+ * (chunk * r, chunk) one of (64, 64), (128, 32), (128, 64), (128, 128), (256, 64), (256, 128), else
+ * PF_ERR_UNSUPPORTED; L a multiple of chunk, else PF_ERR_SHAPE.  With n = chunk * r and
+ * NC = L / chunk, for every (b, h, c):
  *
  *   Cmat = Id + M (.) diag(beta) K K^T,  M[(t,i),(s,j)] = 1 iff s < t     (Theorem 3.2 in delta
  *          variables; Id - M (.) A B^T of the theorem)

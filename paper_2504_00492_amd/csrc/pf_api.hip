@@ -40,9 +40,9 @@ struct WorkspacePlan {
 // and there are enough blocks to cut.  Three passes of the scan kernel then run with
 // `segments` times as many chains; measured, eight segments pay (1.6-1.7x on 4 heads of 65536
 // tokens) and four only break even.
-int scan_segments(int heads, int L, int d, int r, int chunk)
+int scan_segments(int heads, int L, int d, int dv, int r, int chunk)
 {
-    if (L % chunk != 0) return 1;
+    if (L % chunk != 0 || d != dv) return 1;     // (the composition kernel takes square states)
     const int NC = L / chunk;
     const long long chains = (long long)heads * (d / pf::scan_dv_tile(heads, d, chunk * r));
     const int cus = pf::device_cu_count();
@@ -53,15 +53,15 @@ int scan_segments(int heads, int L, int d, int r, int chunk)
 }
 // L tokens per head of which the first L - L % chunk (whole flow blocks) go through the MFMA
 // kernels; when a tail remains, a state buffer carries S from them to the kernel of the tail.
-WorkspacePlan plan_workspace(int heads, int L, int d, int r, int chunk)
+WorkspacePlan plan_workspace(int heads, int L, int d, int dv, int r, int chunk)
 {
     const size_t n = (size_t)chunk * r;
     const size_t tok = (size_t)heads * (L - L % chunk);   // tokens in whole blocks over all heads
     const size_t tb = tok / chunk * n * n * 2;            // Tt: bf16, n*n per block
     const size_t pb = tok * n * 2;                        // Pt: bf16, chunk*n per block
-    const size_t sb = L % chunk ? (size_t)heads * d * d * 4 : 0;
+    const size_t sb = L % chunk ? (size_t)heads * dv * d * 4 : 0;
     WorkspacePlan p;
-    p.segments = scan_segments(heads, L, d, r, chunk);
+    p.segments = scan_segments(heads, L, d, dv, r, chunk);
     const size_t gb = p.segments > 1 ? (size_t)heads * p.segments * d * d * 4 : 0;   // per-segment d x d fp32
     size_t o = 0;
     p.oT = o; o = round_up(o + tb, kAlign);
@@ -78,10 +78,10 @@ WorkspacePlan plan_workspace(int heads, int L, int d, int r, int chunk)
 
 // Tokens per chunk for the generic kernel when it takes the ragged tail of an MFMA-path call:
 // the largest power of two up to 16 whose working set fits LDS next to the fp32 state (0: none).
-int tail_chunk(int d, int r)
+int tail_chunk(int d, int dv, int r)
 {
     for (int c = 16; c >= 1; c /= 2)
-        if (pf::generic_lds_bytes(d, d, r, c) <= pf::kMaxLdsBytes) return c;
+        if (pf::generic_lds_bytes(d, dv, r, c) <= pf::kMaxLdsBytes) return c;
     return 0;
 }
 
@@ -93,7 +93,7 @@ int tail_chunk(int d, int r)
 // largest block that has an instance.  0 when no instance serves these dimensions.
 int mfma_block(int d_k, int d_v, int r, int chunk, pf_dtype dt)
 {
-    if (dt != PF_BF16 || d_k != d_v) return 0;
+    if (dt != PF_BF16 || d_v % 16 != 0) return 0;   // d_k: where an instance exists (64, 128)
     int any = 0;
     for (int c = chunk; c >= 16; c /= 2) {
         if ((long long)c * r <= 4096 && pf::mfma_instance_exists(d_k, c * r, c)) {
@@ -108,7 +108,7 @@ int mfma_block(int d_k, int d_v, int r, int chunk, pf_dtype dt)
 // The split entry points take any (d, chunk * r, chunk) that has an instance.
 bool split_instance(int d_k, int d_v, int r, int chunk)
 {
-    return d_k == d_v && (long long)chunk * r <= 4096 && pf::mfma_instance_exists(d_k, chunk * r, chunk);
+    return d_v % 16 == 0 && (long long)chunk * r <= 4096 && pf::mfma_instance_exists(d_k, chunk * r, chunk);
 }
 
 // Tokens per chunk on the generic path: the requested chunk when its working set fits LDS next
@@ -204,8 +204,8 @@ size_t pf_delta_fwd_workspace_bytes(int B, int H, int L, int d_k, int d_v, int r
     if (family(d_k, d_v, r, chunk, dt) != 2) return 0;
     const int block = mfma_block(d_k, d_v, r, chunk, dt);
     if (L < block) return 0;                         // all of it is tail: generic kernel, no scratch
-    if (L % block != 0 && tail_chunk(d_k, r) == 0) return 0;
-    return plan_workspace(B * H, L, d_k, r, block).total;
+    if (L % block != 0 && tail_chunk(d_k, d_v, r) == 0) return 0;
+    return plan_workspace(B * H, L, d_k, d_v, r, block).total;
 }
 
 size_t pf_delta_fwd_describe(int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt, char *buf,
@@ -222,11 +222,11 @@ size_t pf_delta_fwd_describe(int B, int H, int L, int d_k, int d_v, int r, int c
             out = generic;
         } else {
             const int heads = B * H, n = block * r;
-            const int G = scan_segments(heads, L, d_k, r, block);
+            const int G = scan_segments(heads, L, d_k, d_v, r, block);
             const std::string dims = std::to_string(d_k) + ", " + std::to_string(n) + ", " + std::to_string(block);
             const std::string flow = "pf::flow_kernel<" + dims + ">";
             const std::string scan = "pf::scan_kernel<" + dims + ", " +
-                                     std::to_string(pf::scan_dv_tile(heads * G, d_k, n));
+                                     std::to_string(pf::scan_dv_tile(heads * G, d_v, n));
             if (G > 1)
                 out = flow + ";pf::segment_constants_kernel;" + scan + ", false>;" + scan + ", false>;" +
                       "pf::segment_compose_kernel;" + scan + ", true>";
@@ -257,7 +257,7 @@ static pf_status delta_fwd_impl(const void *Q, const void *K, const void *V, con
     // every head go through the generic kernel, from the state the blocks leave behind.
     const int block = fam == 2 ? mfma_block(d_k, d_v, r, chunk, dt) : generic_block(d_k, d_v, r, chunk);
     const int tail = fam == 2 ? L % block : 0;
-    const int tchunk = tail ? tail_chunk(d_k, r) : 0;
+    const int tchunk = tail ? tail_chunk(d_k, d_v, r) : 0;
     if (tail && tchunk == 0) return PF_ERR_SHAPE;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(beta) || !aligned16(O) ||
         !aligned16(S0) || !aligned16(S_L))
@@ -270,7 +270,7 @@ static pf_status delta_fwd_impl(const void *Q, const void *K, const void *V, con
                                           fam == 1 ? block : (tchunk ? tchunk : 1), dt == PF_BF16, s, 0, product);
         return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
     }
-    const WorkspacePlan wp = plan_workspace(heads, L, d_k, r, block);
+    const WorkspacePlan wp = plan_workspace(heads, L, d_k, d_v, r, block);
     if (!workspace || workspace_bytes < wp.total) return PF_ERR_WORKSPACE;
     if (!aligned16(workspace)) return PF_ERR_ALIGN;
     char *ws = static_cast<char *>(workspace);
@@ -302,7 +302,7 @@ static pf_status delta_fwd_impl(const void *Q, const void *K, const void *V, con
         } else {
             e = pf::launch_chunk_flow(Q, K, beta, ws + wp.oT, ws + wp.oP, heads, L, d_k, r, block, s, product);
             if (e != hipSuccess) return PF_ERR_LAUNCH;
-            e = pf::launch_chunk_scan(Q, K, V, beta, Tt, Pt, S0, O, Smid, heads, L, d_k, r, block, s);
+            e = pf::launch_chunk_scan(Q, K, V, beta, Tt, Pt, S0, O, Smid, heads, L, d_k, r, block, s, 1, 1, d_v);
             if (e != hipSuccess) return PF_ERR_LAUNCH;
         }
         state = Smid;
@@ -450,7 +450,7 @@ pf_status pf_delta_chunk_scan(const void *Q, const void *K, const void *V, const
         !aligned16(Pt) || !aligned16(S0) || !aligned16(O) || !aligned16(S_L))
         return PF_ERR_ALIGN;
     hipError_t e = pf::launch_chunk_scan(Q, K, V, beta, Tt, Pt, S0, O, S_L, B * H, L, d_k, r, chunk,
-                                         static_cast<hipStream_t>(stream));
+                                         static_cast<hipStream_t>(stream), 1, 1, d_v);
     return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
 }
 

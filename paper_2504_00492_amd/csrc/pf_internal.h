@@ -52,10 +52,11 @@ hipError_t launch_chunk_flow(const void *Q, const void *K, const void *beta, voi
 hipError_t launch_chunk_scan(const void *Q, const void *K, const void *V, const void *beta,
                              const void *Tt, const void *Pt, const float *S0, void *O, float *SL,
                              int heads, int L, int d, int r, int chunk, hipStream_t stream,
-                             int vmul = 1, int s0mul = 1);
-// (O may be NULL: the state is advanced and S_L written, nothing is read out.)
-// d_v rows of S one scan workgroup owns for these dimensions (the scan runs heads * d / tile chains)
-int scan_dv_tile(int heads, int d, int n);
+                             int vmul = 1, int s0mul = 1, int dv = 0);
+// (O may be NULL: the state is advanced and S_L written, nothing is read out.  d = d_k; dv = d_v,
+// a multiple of 16, 0 meaning d_v = d_k: V, O are dv wide and S0, S_L are dv x d.)
+// d_v rows of S one scan workgroup owns for these dimensions (the scan runs heads * dv / tile chains)
+int scan_dv_tile(int heads, int dv, int n);
 
 // ---- fused forward (pf_fused.hip): flow and scan of every block in one kernel, d = d_k = d_v,
 // n = chunk * r in {64, 128}.  Takes the first L / chunk whole blocks of every head.  Tdump / Pdump

@@ -2,7 +2,8 @@
 // (arXiv 2504.00492) as a sequential hand-over of S from chunk to chunk.
 //
 // Rows of S evolve independently (the recurrence of Section 3.1 multiplies S from the right),
-// so a workgroup owns TV rows of S (a tile of d_v) of one (b, h) and walks the chunks.  Per
+// so a workgroup owns TV rows of S (a tile of d_v) of one (b, h) and walks the chunks; d_v is a
+// run-time size (any multiple of the tile), only d = d_k is a template parameter.  Per
 // chunk, with T = (Id + G)^{-1} and P = Mbar (.) Q K^T from the chunk-flow kernel:
 //     R     = beta (.) (V - K S_c^T)      n x TV       (the chunk's values seen from the incoming state)
 //     U_eff = T R                         n x TV       (= U' - W S_c^T: U + W S_0^T of Theorem 3.2, sign folded)
@@ -84,7 +85,7 @@ template <int D, int N, int C, int TV, bool RO>
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     const bf16 *__restrict__ Q, const bf16 *__restrict__ K, const bf16 *__restrict__ V,
     const bf16 *__restrict__ beta, const bf16 *__restrict__ Tt, const bf16 *__restrict__ Pt,
-    const float *S0, bf16 *__restrict__ O, float *SL, int nchains, int NC, int tail, int vmul, int s0mul)
+    const float *S0, bf16 *__restrict__ O, float *SL, int nchains, int NC, int tail, int vmul, int s0mul, int dv)
 {
     using Ld = ScanLds<D, N, C, TV>;
     constexpr int R = N / C;
@@ -135,9 +136,9 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     // every chain start from the same d x d matrix at S0 (the identity, for that propagator).
     Q += chain * (size_t)tail * D;
     K += chain * (size_t)tail * R * D;
-    V += (size_t)vmul * chain * (size_t)tail * R * D;
+    V += (size_t)vmul * chain * (size_t)tail * R * dv;
     beta += chain * (size_t)tail * R;
-    if (O) O += chain * (size_t)tail * D;
+    if (O) O += chain * (size_t)tail * dv;
 
     // ------------------------------------------------------------------ state waves
     auto state_wave = [&](auto Wc) {
@@ -155,7 +156,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             for (int nt = 0; nt < NNT; ++nt) {
                 const int mt = W * MPW + a;
                 f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                if (S0) v = *reinterpret_cast<const f32x4 *>(S0 + (size_t)s0mul * chain * (size_t)D * D +
+                if (S0) v = *reinterpret_cast<const f32x4 *>(S0 + (size_t)s0mul * chain * (size_t)dv * D +
                                                              (size_t)(dv0 + 16 * nt + r16) * D + 16 * mt + 4 * g);
                 sacc[a][nt] = v;
                 st4(&Sb[(16 * nt + r16) * SP + 16 * mt + 4 * g], cvt4(v));
@@ -410,7 +411,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             for (int a = 0; a < MPW; ++a)
 #pragma unroll
                 for (int nt = 0; nt < NNT; ++nt)
-                    *reinterpret_cast<f32x4 *>(SL + chain * (size_t)D * D + (size_t)(dv0 + 16 * nt + r16) * D +
+                    *reinterpret_cast<f32x4 *>(SL + chain * (size_t)dv * D + (size_t)(dv0 + 16 * nt + r16) * D +
                                                16 * (W * MPW + a) + 4 * g) = sacc[a][nt];
         }
     };
@@ -452,12 +453,12 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         };
         auto fetch_vqb = [&](size_t cid, auto Sc) {
             constexpr int S = decltype(Sc)::value % kSets;
-            const bf16 *Vg = V + (size_t)vmul * cid * (size_t)N * D + dv0;
+            const bf16 *Vg = V + (size_t)vmul * cid * (size_t)N * dv + dv0;
 #pragma unroll
             for (int q = 0; q < VV; ++q) {
                 int v = tb + NTHR * q;
                 v = v < N * PPR ? v : N * PPR - 1;                 // clamp instead of branching
-                vreg[S][q] = ld8(Vg + (size_t)(v / PPR) * D + (v % PPR) * 8);
+                vreg[S][q] = ld8(Vg + (size_t)(v / PPR) * dv + (v % PPR) * 8);
             }
             breg[S] = beta[cid * (size_t)N + (tb % N)];
         };
@@ -504,12 +505,12 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         // the O tile of one chunk (chunk tokens x TV features), LDS -> its rows of O
         auto copy_out = [&](size_t cid) {
             if constexpr (!RO) return;
-            bf16 *Oc = O + cid * (size_t)C * D;
+            bf16 *Oc = O + cid * (size_t)C * dv;
 #pragma unroll
             for (int q = 0; q < OV; ++q) {
                 const int v = tb + NTHR * q;
                 if ((q + 1) * NTHR <= C * PPR || v < C * PPR)
-                    st8(Oc + (size_t)(v / PPR) * D + dv0 + 8 * (v % PPR), ld8(&Ob[(v / PPR) * OP + 8 * (v % PPR)]));
+                    st8(Oc + (size_t)(v / PPR) * dv + dv0 + 8 * (v % PPR), ld8(&Ob[(v / PPR) * OP + 8 * (v % PPR)]));
             }
         };
 
@@ -652,7 +653,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 template <int D, int N, int C, int TV, bool RO>
 static hipError_t launch_scan_ro(const void *Q, const void *K, const void *V, const void *beta,
                                        const void *Tt, const void *Pt, const float *S0, void *O, float *SL,
-                                       int heads, int NC, int tail, int vmul, int s0mul, hipStream_t stream)
+                                       int heads, int NC, int tail, int vmul, int s0mul, int dv, hipStream_t stream)
 {
     auto kern = scan_kernel<D, N, C, TV, RO>;
     constexpr size_t lds = ScanLds<D, N, C, TV>::total;
@@ -660,45 +661,46 @@ static hipError_t launch_scan_ro(const void *Q, const void *K, const void *V, co
     static std::atomic<uint64_t> armed{0};
     hipError_t e = arm_dynamic_lds(armed, reinterpret_cast<const void *>(kern), lds);
     if (e != hipSuccess) return e;
-    const unsigned grid = (unsigned)heads * (D / TV);
+    const unsigned grid = (unsigned)heads * (dv / TV);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kScanThreads), lds, stream, (const bf16 *)Q,
                        (const bf16 *)K, (const bf16 *)V, (const bf16 *)beta, (const bf16 *)Tt,
-                       (const bf16 *)Pt, S0, (bf16 *)O, SL, heads, NC, tail, vmul, s0mul);
+                       (const bf16 *)Pt, S0, (bf16 *)O, SL, heads, NC, tail, vmul, s0mul, dv);
     return hipGetLastError();
 }
 
-int scan_dv_tile(int heads, int d, int n)
+int scan_dv_tile(int heads, int dv, int n)
 {
     // 32 rows when that already gives at least one workgroup per CU, else 16 rows (twice the
     // workgroups, half the MFMA work per operand byte).  With n = 256 only the 16-row tile
     // fits LDS next to the chunk's K.
-    return (n < 256 && (long long)heads * (d / 32) >= (long long)device_cu_count()) ? 32 : 16;
+    return (n < 256 && dv % 32 == 0 && (long long)heads * (dv / 32) >= (long long)device_cu_count()) ? 32 : 16;
 }
 
 template <int D, int N, int C, int TV>
 static hipError_t launch_scan_instance(const void *Q, const void *K, const void *V, const void *beta,
                                        const void *Tt, const void *Pt, const float *S0, void *O, float *SL,
-                                       int heads, int NC, int tail, int vmul, int s0mul, hipStream_t stream)
+                                       int heads, int NC, int tail, int vmul, int s0mul, int dv, hipStream_t stream)
 {
-    return O ? launch_scan_ro<D, N, C, TV, true>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, stream)
-             : launch_scan_ro<D, N, C, TV, false>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, stream);
+    return O ? launch_scan_ro<D, N, C, TV, true>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, dv, stream)
+             : launch_scan_ro<D, N, C, TV, false>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, dv, stream);
 }
 
 hipError_t launch_chunk_scan(const void *Q, const void *K, const void *V, const void *beta, const void *Tt,
                              const void *Pt, const float *S0, void *O, float *SL, int heads, int L, int d,
-                             int r, int chunk, hipStream_t stream, int vmul, int s0mul)
+                             int r, int chunk, hipStream_t stream, int vmul, int s0mul, int dv)
 {
     const int NC = L / chunk, tail = L % chunk;   // the tail tokens of every head are skipped
     const int n = chunk * r;
-    if ((long long)heads * (d / 16) > 0x7fffffffLL) return hipErrorInvalidValue;
-    const bool wide = scan_dv_tile(heads, d, n) == 32;
+    if (dv <= 0) dv = d;
+    if (dv % 16 != 0 || (long long)heads * (dv / 16) > 0x7fffffffLL) return hipErrorInvalidValue;
+    const bool wide = scan_dv_tile(heads, dv, n) == 32;
 #define X(DD, NN, CC)                                                                                      \
     if (d == DD && n == NN && chunk == CC) {                                                                \
         if constexpr (NN < 256) {                                                                           \
             if (wide)                                                                                       \
-                return launch_scan_instance<DD, NN, CC, 32>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, stream); \
+                return launch_scan_instance<DD, NN, CC, 32>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, dv, stream); \
         }                                                                                                   \
-        return launch_scan_instance<DD, NN, CC, 16>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, stream);   \
+        return launch_scan_instance<DD, NN, CC, 16>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, dv, stream);   \
     }
     PF_SCAN_INSTANCES(X)
 #undef X

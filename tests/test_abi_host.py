@@ -57,7 +57,8 @@ def test_flow_block(pf):
             == pf.pf_delta_fwd_workspace_bytes(2, 16, 8192, 128, 128, 4, 64, BF))
     # the split entry points take every (chunk * r, chunk) that has an instance, and nothing else
     assert pf.pf_delta_chunk_supported(128, 128, 2, 128) == 1 and pf.pf_delta_chunk_supported(128, 128, 4, 64) == 1
-    assert pf.pf_delta_chunk_supported(128, 128, 4, 128) == 0 and pf.pf_delta_chunk_supported(128, 64, 1, 64) == 0
+    assert pf.pf_delta_chunk_supported(128, 128, 4, 128) == 0 and pf.pf_delta_chunk_supported(128, 72, 1, 64) == 0
+    assert pf.pf_delta_chunk_supported(128, 64, 1, 64) == 1 and pf.pf_delta_chunk_supported(96, 96, 1, 64) == 0
     fake = 0x1000
     assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 256, 128, 128, 4, 128, 0) == pf.PF_ERR_UNSUPPORTED
     assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 256, 128, 128, 2, 32, 0) == pf.PF_ERR_UNSUPPORTED
@@ -127,6 +128,10 @@ def test_supported_families(pf):
     assert pf.pf_delta_fwd_block(16, 16, 1, 16, F32) == 16             # fits as requested
     assert pf.pf_delta_fwd_supported(256, 256, 1, 8, F32) == 0         # the fp32 state alone exceeds LDS
     assert pf.pf_delta_fwd_supported(20, 12, 3, 8, BF) == 1            # odd shape -> generic
+    assert pf.pf_delta_fwd_supported(128, 64, 2, 64, BF) == 2          # d_v != d_k: MFMA path, d_v tiles of 16 / 32 rows
+    assert pf.pf_delta_fwd_supported(64, 48, 1, 64, BF) == 2
+    assert pf.pf_delta_fwd_supported(64, 40, 1, 64, BF) == 1           # d_v not a multiple of 16 -> generic
+    assert pf.pf_delta_fwd_supported(96, 128, 1, 64, BF) == 1          # d_k without an instance -> generic
     assert pf.pf_delta_fwd_supported(0, 16, 1, 16, F32) == 0
     assert pf.pf_delta_fwd_supported(16, 16, 1, 16, 7) == 0
 
@@ -200,7 +205,7 @@ def test_argument_checks_return_before_launch(pf):
     assert flow(A, A, A, A + 2, A, 1, 1, 128, 128, 128, 2, 64, 0) == pf.PF_ERR_ALIGN
     scan = pf.pf_delta_chunk_scan
     assert scan(A, A, A, A, A, A, A, None, A, 1, 1, 128, 128, 128, 2, 64, 0) == pf.PF_ERR_NULL
-    assert scan(A, A, A, A, A, A, A, A, A, 1, 1, 128, 128, 64, 2, 64, 0) == pf.PF_ERR_UNSUPPORTED
+    assert scan(A, A, A, A, A, A, A, A, A, 1, 1, 128, 128, 72, 2, 64, 0) == pf.PF_ERR_UNSUPPORTED   # d_v not a multiple of 16
     assert scan(A, A, A, A, A, A, A, A, A + 4, 1, 1, 128, 128, 128, 2, 64, 0) == pf.PF_ERR_ALIGN
 
 

@@ -164,6 +164,20 @@ def test_mfma_other_instances(pf, oracle, d, r, C):
     _check(pf, oracle, w, expect_family=2)
 
 
+@pytest.mark.parametrize("kw", [
+    dict(B=1, H=3, L=256, d_k=128, d_v=64, r=2, chunk=64),                 # d_v < d_k
+    dict(B=1, H=2, L=192, d_k=64, d_v=128, r=1, chunk=64, s0_std=0.2),     # d_v > d_k, S0 is 128 x 64
+    dict(B=1, H=2, L=160, d_k=128, d_v=48, r=4, chunk=32),                 # d_v = 48: three 16-row tiles
+    dict(B=4, H=8, L=128, d_k=64, d_v=256, r=2, chunk=64, s0_std=0.1),     # 32 heads x 8 tiles of 32 rows
+    dict(B=1, H=2, L=229, d_k=128, d_v=64, r=2, chunk=64, s0_std=0.1),     # ragged tail through the generic kernel
+    dict(B=1, H=2, L=256, d_k=128, d_v=32, r=2, chunk=128),                # blocks of 256 virtual tokens -> 64 tokens
+])
+def test_mfma_path_dv_differs_from_dk(pf, oracle, kw):
+    """The state is d_v x d_k; only d_k is a compile-time size of the MFMA kernels."""
+    w = synth.Workload("dvdk", "bf16", seed=61, **{"s0_std": 0.0, "reflect_frac": 0.05, **kw})
+    _check(pf, oracle, w, expect_family=2)
+
+
 def test_mfma_single_chunk_and_beta_zero(pf, oracle):
     import torch
     w = synth.WORKLOADS["cfg2"].with_(B=1, H=2, L=64, s0_std=0.2)
