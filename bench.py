@@ -24,7 +24,9 @@ cfg3a, cfg3b), each with its own K timed steps.  Per workload:
   * "requested_chunk": where pf_delta_fwd runs flow blocks shorter than the requested chunk, the
     two kernels timed at the requested chunk itself through the split entry points (null when no
     instance of that size exists);
-  * "fused_kernel": the one-kernel forward (pf_delta_fwd_fused) on the same blocks.
+  * "fused_kernel": the one-kernel forward (pf_delta_fwd_fused) on the same blocks;
+  * "general_drivers": the same forward through the general-driver kernels (pf_flow_fwd_mfma) on
+    drivers of the same shape (A = -K / 2, Atil = V, B = K: two operand arrays instead of one).
 "cpu_baseline": the fp64 oracle (oracle/, untuned) timed on this machine's host cores on a stated
 sample of the headline workload, with the parity of the GPU result on that sample.
 Only one GPU is used; --gpus N with N > 1 exits with a message.
@@ -192,7 +194,7 @@ def run_workload(pf, torch, w, inputs, args, traffic_table):
     min_bytes = min_bytes_per_token_head(dk, r, e) * token_heads
     alg_tflops = f_alg * token_heads / (ms_per_step * 1e-3) / 1e12
 
-    kernels, requested, fused = {}, None, None
+    kernels, requested, fused, general = {}, None, None, None
     if fam == 2:
         dims = (B, H, L, dk, dv, r)
         nwarm = min(args.warmup + settle_steps, 200)
@@ -249,6 +251,25 @@ def run_workload(pf, torch, w, inputs, args, traffic_table):
                      "frac_hbm_peak": min_bytes / (t_fused * 1e-3) / 1e9 / PEAK_HBM_GBS}
             step(0)
             torch.cuda.synchronize()
+        gblock = pf.pf_flow_fwd_mfma_block(dk, dv, r, C, dt)
+        if gblock:
+            gneed = pf.pf_flow_fwd_mfma_workspace_bytes(B, H, L, dk, dv, r, C, dt)
+            gws = torch.empty(max(gneed, 16), dtype=torch.uint8, device=dev)
+            Ag = (K * -0.5).contiguous()
+            nrep = max(10, args.steps // 4)
+            evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(nrep)]
+            for i in range(5 + nrep):
+                if i >= 5:
+                    evs[i - 5][0].record(stream)
+                st = pf.pf_flow_fwd_mfma(Q, Ag, V, K, S0, O, SL, B, H, L, dk, dv, r, C, dt, gws, gneed, stream)
+                assert st == pf.PF_OK, st
+                if i >= 5:
+                    evs[i - 5][1].record(stream)
+            torch.cuda.synchronize()
+            general = {"ms": sum(a.elapsed_time(b) for a, b in evs) / nrep, "block": gblock}
+            del gws, Ag
+            step(0)
+            torch.cuda.synchronize()
     else:
         tfl = f_alg * token_heads / (ms_per_step * 1e-3) / 1e12
         roofline = {"bound": "alu", "kernel": "generic_kernel", "kernel_name": launched[0] if launched else None,
@@ -267,6 +288,7 @@ def run_workload(pf, torch, w, inputs, args, traffic_table):
         "min_hbm_gbs": min_bytes / (ms_per_step * 1e-3) / 1e9,
         "frac_hbm_peak_min_traffic": min_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "kernels": kernels, "roofline": roofline, "requested_chunk": requested, "fused_kernel": fused,
+        "general_drivers": general,
         # inputs + outputs + workspace of one step; when that is below the last-level cache the
         # inputs are rotated over several copies so that each step reads them from HBM
         "working_set_bytes": int(min_bytes + need + B * H * dv * dk * 4),

@@ -228,6 +228,28 @@ pf_status pf_flow_fwd(const void *Q, const void *A, const void *Atil, const void
                       pf_stream stream);
 
 /*
+ * pf_flow_fwd on the MFMA kernels (PF_BF16 only): the chunk flow of Theorem 3.2 as printed, with
+ * the system matrix Id - M (.) A B^T built from two operand arrays (rows from A, columns from B), its
+ * inverse T by the same block substitution, P = Mbar (.) Q B^T, and per block
+ *
+ *   U_eff = T (Atil + A S_c^T),   O_c = Q S_c^T + P U_eff,   S_c+1 = S_c + U_eff^T B .
+ *
+ * d_k in {64, 128}, d_v a multiple of 16, flow blocks of at most 128 virtual tokens:
+ * pf_flow_fwd_mfma_block returns the block used (chunk / 2^j for the smallest j with block * r <= 128
+ * and a kernel instance), 0 when none exists (then PF_ERR_UNSUPPORTED: use pf_flow_fwd).  Any L: the
+ * L % block tokens at the end of every (b, h) go through the generic kernel.  workspace: at least
+ * pf_flow_fwd_mfma_workspace_bytes(...) bytes of device scratch, overwritten.  Arguments otherwise as
+ * pf_flow_fwd, errors as pf_delta_fwd.
+ */
+int pf_flow_fwd_mfma_block(int d_k, int d_v, int r, int chunk, pf_dtype dt);
+size_t pf_flow_fwd_mfma_workspace_bytes(int B, int H, int L, int d_k, int d_v, int r, int chunk,
+                                        pf_dtype dt);
+pf_status pf_flow_fwd_mfma(const void *Q, const void *A, const void *Atil, const void *Bm,
+                           const float *S0, void *O, float *S_L,
+                           int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt,
+                           void *workspace, size_t workspace_bytes, pf_stream stream);
+
+/*
  * Step 2 of Section 3 on its own ("parallel compute": the flow of every chunk, no dependence
  * between chunks), MFMA path only: d_k in {64, 128}, d_v a multiple of 16 (the flow does not depend on
  * d_v; the argument is checked so that both split entry points accept the same dimensions) and

@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libpf.so")
 PF_F32, PF_BF16 = 0, 1
 
 EXPORTS = ["pf_version", "pf_status_str", "pf_delta_fwd_supported", "pf_delta_fwd_block", "pf_delta_fwd_workspace_bytes",
-           "pf_delta_fwd_describe", "pf_delta_fwd", "pf_init", "pf_delta_fwd_static_limit", "pf_delta_fwd_static", "pf_delta_product_fwd", "pf_delta_fwd_fused_supported", "pf_delta_fwd_fused", "pf_beta_exponential", "pf_flow_fwd_supported", "pf_flow_fwd", "pf_delta_chunk_supported", "pf_delta_chunk_flow", "pf_delta_chunk_scan",
+           "pf_delta_fwd_describe", "pf_delta_fwd", "pf_init", "pf_delta_fwd_static_limit", "pf_delta_fwd_static", "pf_delta_product_fwd", "pf_delta_fwd_fused_supported", "pf_delta_fwd_fused", "pf_beta_exponential", "pf_flow_fwd_supported", "pf_flow_fwd", "pf_flow_fwd_mfma_block", "pf_flow_fwd_mfma_workspace_bytes", "pf_flow_fwd_mfma", "pf_delta_chunk_supported", "pf_delta_chunk_flow", "pf_delta_chunk_scan",
            "pf_delta_chunk_sigdelta_supported", "pf_delta_chunk_sigdelta_workspace_bytes", "pf_delta_chunk_sigdelta"]
 
 
@@ -63,6 +63,12 @@ def _load() -> ctypes.CDLL:
     lib.pf_flow_fwd_supported.argtypes = [i, i, i, i, i]
     lib.pf_flow_fwd.restype = i
     lib.pf_flow_fwd.argtypes = [vp] * 7 + [i] * 8 + [vp]
+    lib.pf_flow_fwd_mfma_block.restype = i
+    lib.pf_flow_fwd_mfma_block.argtypes = [i] * 5
+    lib.pf_flow_fwd_mfma_workspace_bytes.restype = sz
+    lib.pf_flow_fwd_mfma_workspace_bytes.argtypes = [i] * 8
+    lib.pf_flow_fwd_mfma.restype = i
+    lib.pf_flow_fwd_mfma.argtypes = [vp] * 7 + [i] * 8 + [vp, sz, vp]
     lib.pf_delta_chunk_supported.restype = i
     lib.pf_delta_chunk_supported.argtypes = [i] * 4
     lib.pf_delta_chunk_flow.restype = i
@@ -182,6 +188,22 @@ def pf_flow_fwd(Q, A, Atil, Bm, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, str
     """Raw call; returns the pf_status.  Pointers may be torch tensors, ints or None."""
     return int(_lib.pf_flow_fwd(_ptr(Q), _ptr(A), _ptr(Atil), _ptr(Bm), _ptr(S0), _ptr(O), _ptr(S_L),
                                 B, H, L, d_k, d_v, r, chunk, dt, _stream_handle(stream)))
+
+
+def pf_flow_fwd_mfma_block(d_k, d_v, r, chunk, dt) -> int:
+    return int(_lib.pf_flow_fwd_mfma_block(d_k, d_v, r, chunk, dt))
+
+
+def pf_flow_fwd_mfma_workspace_bytes(B, H, L, d_k, d_v, r, chunk, dt) -> int:
+    return int(_lib.pf_flow_fwd_mfma_workspace_bytes(B, H, L, d_k, d_v, r, chunk, dt))
+
+
+def pf_flow_fwd_mfma(Q, A, Atil, Bm, S0, O, S_L, B, H, L, d_k, d_v, r, chunk, dt, workspace, workspace_bytes,
+                     stream=None) -> int:
+    """Raw call; returns the pf_status.  Pointers may be torch tensors, ints or None."""
+    return int(_lib.pf_flow_fwd_mfma(_ptr(Q), _ptr(A), _ptr(Atil), _ptr(Bm), _ptr(S0), _ptr(O), _ptr(S_L),
+                                     B, H, L, d_k, d_v, r, chunk, dt, _ptr(workspace), workspace_bytes,
+                                     _stream_handle(stream)))
 
 
 def pf_delta_chunk_supported(d_k, d_v, r, chunk) -> int:

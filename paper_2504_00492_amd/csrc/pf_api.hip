@@ -105,6 +105,17 @@ int mfma_block(int d_k, int d_v, int r, int chunk, pf_dtype dt)
     return any;
 }
 
+// The same choice for the general drivers: blocks of at most 128 virtual tokens only.
+int mfma_general_block(int d_k, int d_v, int r, int chunk, pf_dtype dt)
+{
+    if (dt != PF_BF16 || d_v % 16 != 0) return 0;
+    for (int c = chunk; c >= 16; c /= 2) {
+        if ((long long)c * r <= 128 && pf::mfma_general_instance_exists(d_k, c * r, c)) return c;
+        if (c % 2 != 0) break;
+    }
+    return 0;
+}
+
 // The split entry points take any (d, chunk * r, chunk) that has an instance.
 bool split_instance(int d_k, int d_v, int r, int chunk)
 {
@@ -396,6 +407,64 @@ int pf_flow_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt)
     if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return 0;
     if (dt != PF_F32 && dt != PF_BF16) return 0;
     return generic_block(d_k, d_v, r, chunk) > 0 ? 1 : 0;
+}
+
+int pf_flow_fwd_mfma_block(int d_k, int d_v, int r, int chunk, pf_dtype dt)
+{
+    if (d_k <= 0 || d_v <= 0 || r <= 0 || chunk <= 0) return 0;
+    return mfma_general_block(d_k, d_v, r, chunk, dt);
+}
+
+size_t pf_flow_fwd_mfma_workspace_bytes(int B, int H, int L, int d_k, int d_v, int r, int chunk, pf_dtype dt)
+{
+    if (check_dims(B, H, L, d_k, d_v, r, chunk) != PF_OK) return 0;
+    const int block = pf_flow_fwd_mfma_block(d_k, d_v, r, chunk, dt);
+    if (block == 0 || L < block) return 0;
+    const size_t n = (size_t)block * r, heads = (size_t)B * H;
+    const size_t tok = heads * (L - L % block);
+    size_t o = round_up(tok / block * n * n * 2, kAlign);          // T of every block
+    o = round_up(o + tok * n * 2, kAlign);                         // P of every block
+    if (L % block) o = round_up(o + heads * d_v * d_k * 4, kAlign);   // the state handed to the tail
+    return o;
+}
+
+pf_status pf_flow_fwd_mfma(const void *Q, const void *A, const void *Atil, const void *Bm, const float *S0,
+                           void *O, float *S_L, int B, int H, int L, int d_k, int d_v, int r, int chunk,
+                           pf_dtype dt, void *workspace, size_t workspace_bytes, pf_stream stream)
+{
+    if (L != 0 && (!Q || !A || !Atil || !Bm || !O)) return PF_ERR_NULL;
+    pf_status st = check_dims(B, H, L, d_k, d_v, r, chunk);
+    if (st != PF_OK) return st;
+    const int block = pf_flow_fwd_mfma_block(d_k, d_v, r, chunk, dt);
+    if (block == 0) return PF_ERR_UNSUPPORTED;
+    const int tail = L % block;
+    const int tchunk = tail_chunk(d_k, d_v, r);
+    if ((tail || L < block) && tchunk == 0) return PF_ERR_SHAPE;
+    if (!aligned16(Q) || !aligned16(A) || !aligned16(Atil) || !aligned16(Bm) || !aligned16(O) ||
+        !aligned16(S0) || !aligned16(S_L))
+        return PF_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int heads = B * H;
+    if (L < block) {
+        hipError_t e = pf::launch_generic_drivers(Q, A, Atil, Bm, S0, O, S_L, heads, L, d_k, d_v, r, tchunk, true, s);
+        return e == hipSuccess ? PF_OK : PF_ERR_LAUNCH;
+    }
+    const size_t need = pf_flow_fwd_mfma_workspace_bytes(B, H, L, d_k, d_v, r, chunk, dt);
+    if (!workspace || workspace_bytes < need) return PF_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return PF_ERR_ALIGN;
+    char *ws = static_cast<char *>(workspace);
+    const size_t n = (size_t)block * r, tok = (size_t)heads * (L - tail);
+    char *Tt = ws, *Pt = ws + round_up(tok / block * n * n * 2, kAlign);
+    float *Smid = tail ? reinterpret_cast<float *>(Pt + round_up(tok * n * 2, kAlign)) : S_L;
+    hipError_t e = pf::launch_chunk_flow_general(Q, A, Bm, Tt, Pt, heads, L, d_k, r, block, s);
+    if (e != hipSuccess) return PF_ERR_LAUNCH;
+    e = pf::launch_chunk_scan_general(Q, A, Atil, Bm, Tt, Pt, S0, O, Smid, heads, L, d_k, d_v, r, block, s);
+    if (e != hipSuccess) return PF_ERR_LAUNCH;
+    if (tail) {
+        e = pf::launch_generic_drivers(Q, A, Atil, Bm, Smid, O, S_L, heads, L, d_k, d_v, r, tchunk, true, s, L - tail);
+        if (e != hipSuccess) return PF_ERR_LAUNCH;
+    }
+    return PF_OK;
 }
 
 pf_status pf_flow_fwd(const void *Q, const void *A, const void *Atil, const void *Bm, const float *S0,

@@ -40,15 +40,17 @@ namespace pf {
 constexpr int kFlowThreads = 512;
 constexpr int kFlowWaves = kFlowThreads / 64;
 
-template <int D, int N, int C>
+// GEN: general drivers (A, Atil, B) of Section 3.1 instead of the delta mapping: the rows of the
+// system matrix come from A and its columns from B, so two n x d arrays are resident instead of K.
+template <int D, int N, int C, bool GEN = false>
 struct FlowLds {
     static constexpr int NB = N / 32;       // 32-row blocks per chunk
     static constexpr int KP = D + 8;        // pitch of K / Q rows (bf16)
     static constexpr int GP = N + 8;        // pitch of a row of a G^T block-column (bf16)
     static constexpr int TP = 40;           // pitch of a T_jj^T row (bf16)
     static constexpr int NP = 36;           // pitch of the fp32 scratch used to build T_jj
-    static constexpr size_t oKs = 0;
-    static constexpr size_t oBs = oKs + (size_t)N * KP * 2;
+    static constexpr size_t oKs = 0;                                    // K; with GEN: B, then A
+    static constexpr size_t oBs = oKs + (size_t)(GEN ? 2 : 1) * N * KP * 2;
     static constexpr size_t oTs = oBs + (size_t)N * 4;
     static constexpr size_t oUn = oTs + (size_t)NB * 32 * TP * 2;       // region reused by phase
     // phase "build T_jj": fp32 scratch, one 32 x NP tile per wave that has a diagonal block
@@ -61,12 +63,14 @@ struct FlowLds {
     static constexpr size_t total = oUn + szUn;
 };
 
-template <int D, int N, int C>
+template <int D, int N, int C, bool GEN = false>
 __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
     const bf16 *__restrict__ Q, const bf16 *__restrict__ K, const bf16 *__restrict__ beta,
     bf16 *__restrict__ Tt, bf16 *__restrict__ Pt, int nchunks, int NC, int tail, int mask_shift)
 {
-    using Ld = FlowLds<D, N, C>;
+    // With GEN, K is the array of B rows and `beta` the array of A rows (n x d, like K); the
+    // system matrix is Id - M (.) A B^T and P = Mbar (.) Q B^T (Theorem 3.2 as printed).
+    using Ld = FlowLds<D, N, C, GEN>;
     constexpr int R = N / C;          // rank: virtual tokens per token
     constexpr int NB = Ld::NB;
     constexpr int NKS = D / 32, NKT = N / 32, CT = C / 16;
@@ -78,7 +82,8 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
     static_assert(SPW <= 2, "a wave owns at most two slices");
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    bf16 *Ks = reinterpret_cast<bf16 *>(smem + Ld::oKs);
+    bf16 *Ks = reinterpret_cast<bf16 *>(smem + Ld::oKs);             // column side of the Gram: K, or B
+    bf16 *As = GEN ? Ks + N * KP : Ks;                               // row side: K, or A
     float *bs = reinterpret_cast<float *>(smem + Ld::oBs);
     bf16 *Ts = reinterpret_cast<bf16 *>(smem + Ld::oTs);
     float *NsAll = reinterpret_cast<float *>(smem + Ld::oUn);
@@ -91,7 +96,7 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
     constexpr int VPR = D / 8;                         // 16-byte vectors per row
     constexpr int KV = (N * D / 8 + NTHR - 1) / NTHR;  // vectors of K per thread
     constexpr int QV = (C * D / 8 + NTHR - 1) / NTHR;  // vectors of Q per thread
-    bf16x8 kreg[KV], qreg[QV];
+    bf16x8 kreg[KV], qreg[QV], areg[GEN ? KV : 1];
     bf16 breg = (bf16)0.0f;   // kept as loaded: converting here would wait for the fetch
     static_assert(N <= NTHR, "beta of a chunk is fetched by one pass");
 
@@ -103,9 +108,13 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
 #pragma unroll
         for (int q = 0; q < KV; ++q) {
             const int v = tid0 + NTHR * q;
-            if ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8) kreg[q] = ld8(Kg + (size_t)v * 8);
+            if ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8) {
+                kreg[q] = ld8(Kg + (size_t)v * 8);
+                if constexpr (GEN) areg[q] = ld8(beta + (c * (size_t)N + skew(c) * R) * D + (size_t)v * 8);
+            }
         }
-        breg = beta[c * (size_t)N + skew(c) * R + (tid0 % N)];   // every thread loads: no branch, always in range
+        if constexpr (!GEN)
+            breg = beta[c * (size_t)N + skew(c) * R + (tid0 % N)];   // every thread loads: no branch, always in range
     };
     auto fetch_q = [&](size_t c) {
         const bf16 *Qg = Q + (c * (size_t)C + skew(c)) * D;
@@ -140,9 +149,14 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
 #pragma unroll
         for (int q = 0; q < KV; ++q) {
             const int v = tid + NTHR * q;
-            if ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8) st8(&Ks[(v / VPR) * KP + (v % VPR) * 8], kreg[q]);
+            if ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8) {
+                st8(&Ks[(v / VPR) * KP + (v % VPR) * 8], kreg[q]);
+                if constexpr (GEN) st8(&As[(v / VPR) * KP + (v % VPR) * 8], areg[q]);
+            }
         }
-        if (tid < N) bs[tid] = (float)breg;
+        // the row factor of the system matrix: beta_i for the delta rule (G_ij = beta_i k_i . k_j);
+        // -1 for general drivers (G_ij = -a_i . b_j)
+        if (tid < N) bs[tid] = GEN ? -1.0f : (float)breg;
         __syncthreads();
         fetch_k(nxt);
 
@@ -160,9 +174,14 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
                 for (int ks = 0; ks < NKS; ++ks) {
                     bf16x8 k0 = ld8(&Ks[(32 * db + r16) * KP + 32 * ks + 8 * g]);
                     bf16x8 k1 = ld8(&Ks[(32 * db + 16 + r16) * KP + 32 * ks + 8 * g]);
-                    acc[0] = mfma16(k0, k0, acc[0]);   // rows 0-15,  cols 0-15
-                    acc[1] = mfma16(k1, k0, acc[1]);   // rows 16-31, cols 0-15
-                    acc[2] = mfma16(k1, k1, acc[2]);   // rows 16-31, cols 16-31
+                    bf16x8 a0 = k0, a1 = k1;
+                    if constexpr (GEN) {
+                        a0 = ld8(&As[(32 * db + r16) * KP + 32 * ks + 8 * g]);
+                        a1 = ld8(&As[(32 * db + 16 + r16) * KP + 32 * ks + 8 * g]);
+                    }
+                    acc[0] = mfma16(a0, k0, acc[0]);   // rows 0-15,  cols 0-15
+                    acc[1] = mfma16(a1, k0, acc[1]);   // rows 16-31, cols 0-15
+                    acc[2] = mfma16(a1, k1, acc[2]);   // rows 16-31, cols 16-31
                 }
 #pragma unroll
                 for (int tile = 0; tile < 4; ++tile) {
@@ -258,8 +277,8 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
                 f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < NKS; ++ks) {
-                    acc0 = mfma16(ld8(&Ks[(16 * at + r16) * KP + 32 * ks + 8 * g]), bk[ks], acc0);
-                    acc1 = mfma16(ld8(&Ks[(16 * at2 + r16) * KP + 32 * ks + 8 * g]), bk[ks], acc1);
+                    acc0 = mfma16(ld8(&As[(16 * at + r16) * KP + 32 * ks + 8 * g]), bk[ks], acc0);
+                    acc1 = mfma16(ld8(&As[(16 * at2 + r16) * KP + 32 * ks + 8 * g]), bk[ks], acc1);
                 }
                 f32x4 nb0, nb1;
 #pragma unroll
@@ -372,15 +391,15 @@ bool mfma_instance_exists(int d, int n, int chunk)
     return false;
 }
 
-template <int D, int N, int C>
+template <int D, int N, int C, bool GEN = false>
 static hipError_t launch_flow_instance(const void *Q, const void *K, const void *beta, void *Tt, void *Pt,
                                        size_t nchunks, int NC, int tail, bool product, hipStream_t stream)
 {
-    auto kern = flow_kernel<D, N, C>;
+    auto kern = flow_kernel<D, N, C, GEN>;
     int mask_shift = 0;
     if (!product)
         while ((1 << mask_shift) < N / C) ++mask_shift;
-    constexpr size_t lds = FlowLds<D, N, C>::total;
+    constexpr size_t lds = FlowLds<D, N, C, GEN>::total;
     static_assert(lds <= kMaxLdsBytes, "flow kernel LDS plan exceeds the CU");
     static std::atomic<uint64_t> armed{0};
     hipError_t e = arm_dynamic_lds(armed, reinterpret_cast<const void *>(kern), lds);
@@ -406,6 +425,26 @@ hipError_t launch_chunk_flow(const void *Q, const void *K, const void *beta, voi
 #define X(DD, NN, CC)                                                                        \
     if (d == DD && n == NN && chunk == CC)                                                    \
         return launch_flow_instance<DD, NN, CC>(Q, K, beta, Tt, Pt, nchunks, NC, tail, product, stream);
+    PF_FLOW_INSTANCES(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+bool mfma_general_instance_exists(int d, int n, int chunk) { return n <= 128 && mfma_instance_exists(d, n, chunk); }
+
+hipError_t launch_chunk_flow_general(const void *Q, const void *A, const void *Bm, void *Tt, void *Pt, int heads,
+                                     int L, int d, int r, int chunk, hipStream_t stream)
+{
+    const int NC = L / chunk, tail = L % chunk;   // the tail tokens of every head are skipped
+    const size_t nchunks = (size_t)heads * NC;
+    if (nchunks == 0) return hipSuccess;
+    if (nchunks > 0x7fffffffull) return hipErrorInvalidValue;
+    const int n = chunk * r;
+#define X(DD, NN, CC)                                                                                    \
+    if constexpr (NN <= 128) {                                                                            \
+        if (d == DD && n == NN && chunk == CC)                                                            \
+            return launch_flow_instance<DD, NN, CC, true>(Q, Bm, A, Tt, Pt, nchunks, NC, tail, false, stream); \
+    }
     PF_FLOW_INSTANCES(X)
 #undef X
     return hipErrorInvalidValue;

@@ -207,10 +207,10 @@ hipError_t launch_generic(const void *Q, const void *K, const void *V, const voi
 
 hipError_t launch_generic_drivers(const void *Q, const void *A, const void *Atil, const void *Bm, const float *S0,
                                   void *O, float *SL, int heads, int L, int dk, int dv, int r, int chunk,
-                                  bool is_bf16, hipStream_t stream)
+                                  bool is_bf16, hipStream_t stream, int t0)
 {
-    return is_bf16 ? launch_generic_instance<uint16_t, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, 0, false, stream)
-                   : launch_generic_instance<float, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, 0, false, stream);
+    return is_bf16 ? launch_generic_instance<uint16_t, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, t0, false, stream)
+                   : launch_generic_instance<float, true>(Q, Bm, Atil, A, S0, O, SL, heads, L, dk, dv, r, chunk, t0, false, stream);
 }
 
 }  // namespace pf

@@ -41,7 +41,7 @@ hipError_t launch_generic(const void *Q, const void *K, const void *V, const voi
 // general drivers (A, Atil, B) of Section 3.1 through the same kernel
 hipError_t launch_generic_drivers(const void *Q, const void *A, const void *Atil, const void *Bm,
                                   const float *S0, void *O, float *SL, int heads, int L, int dk, int dv,
-                                  int r, int chunk, bool is_bf16, hipStream_t stream);
+                                  int r, int chunk, bool is_bf16, hipStream_t stream, int t0 = 0);
 
 // ---- MFMA path (pf_flow.hip, pf_scan.hip); d = d_k = d_v, n = chunk * r.  Both launchers take
 // the first L / chunk whole blocks of every head (heads L tokens apart) and leave the tail alone.
@@ -53,6 +53,14 @@ hipError_t launch_chunk_scan(const void *Q, const void *K, const void *V, const 
                              const void *Tt, const void *Pt, const float *S0, void *O, float *SL,
                              int heads, int L, int d, int r, int chunk, hipStream_t stream,
                              int vmul = 1, int s0mul = 1, int dv = 0);
+// The same two kernels for the general drivers (A, Atil, B) of Section 3.1 (rows of A, B: d wide,
+// of Atil: dv wide); instances with at most 128 virtual tokens per block.
+bool mfma_general_instance_exists(int d, int n, int chunk);
+hipError_t launch_chunk_flow_general(const void *Q, const void *A, const void *Bm, void *Tt, void *Pt, int heads,
+                                     int L, int d, int r, int chunk, hipStream_t stream);
+hipError_t launch_chunk_scan_general(const void *Q, const void *A, const void *Atil, const void *Bm, const void *Tt,
+                                     const void *Pt, const float *S0, void *O, float *SL, int heads, int L, int d,
+                                     int dv, int r, int chunk, hipStream_t stream);
 // (O may be NULL: the state is advanced and S_L written, nothing is read out.  d = d_k; dv = d_v,
 // a multiple of 16, 0 meaning d_v = d_k: V, O are dv wide and S0, S_L are dv x d.)
 // d_v rows of S one scan workgroup owns for these dimensions (the scan runs heads * dv / tile chains)

@@ -58,14 +58,17 @@ constexpr int kScanRoleWaves = 4;                       // waves per role
 constexpr int kScanRoleThreads = 64 * kScanRoleWaves;
 constexpr int kScanThreads = 2 * kScanRoleThreads;
 
-template <int D, int N, int C, int TV>
+// GEN: general drivers (A, Atil, B) of Section 3.1 instead of the delta mapping.  The state is
+// multiplied by A rows in interval 0 and updated with B rows in interval 2, so a "K buffer" then
+// holds two n x d planes: B first (where K sits otherwise), then A.
+template <int D, int N, int C, int TV, bool GEN = false>
 struct ScanLds {
     static constexpr int KP = D + 8;   // pitch of a row of K
     static constexpr int VP = TV + 8;  // pitch of a row (virtual token) of the V tile
     static constexpr int SP = D + 8;   // pitch of a row of the bf16 state copy
     static constexpr int UP = N + 8;   // pitch of a row of R^T / U_eff^T
     static constexpr int OP = TV + 8;  // pitch of a row (one token) of the staged O tile
-    static constexpr size_t szK = (size_t)N * KP * 2;
+    static constexpr size_t szK = (size_t)(GEN ? 2 : 1) * N * KP * 2;
     static constexpr size_t rest = (size_t)N * VP * 2 + (size_t)N * 4 +
                                    (size_t)TV * SP * 2 + (size_t)2 * TV * UP * 2 + (size_t)C * OP * 2;
     static constexpr bool kDoubleK = 2 * szK + rest <= (size_t)kMaxLdsBytes;
@@ -81,13 +84,16 @@ struct ScanLds {
 
 // RO: the readout O is wanted (false: only the state is advanced, for the per-segment passes of
 // the segment-parallel scan).
-template <int D, int N, int C, int TV, bool RO>
+template <int D, int N, int C, int TV, bool RO, bool GEN = false>
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     const bf16 *__restrict__ Q, const bf16 *__restrict__ K, const bf16 *__restrict__ V,
     const bf16 *__restrict__ beta, const bf16 *__restrict__ Tt, const bf16 *__restrict__ Pt,
     const float *S0, bf16 *__restrict__ O, float *SL, int nchains, int NC, int tail, int vmul, int s0mul, int dv)
 {
-    using Ld = ScanLds<D, N, C, TV>;
+    // With GEN, K is the array of B rows, `beta` the array of A rows (n x d each) and V the array
+    // of Atil rows: R = Atil + A S^T, U_eff = T R, S += U_eff^T B, O = Q S^T + P U_eff.
+    using Ld = ScanLds<D, N, C, TV, GEN>;
+    constexpr int KBUF = (int)(Ld::szK / 2);   // elements of one K buffer (both planes with GEN)
     constexpr int R = N / C;
     constexpr int NKS = D / 32;        // k-steps over d
     constexpr int NKT = N / 32;        // k-steps over the chunk's virtual tokens
@@ -104,7 +110,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     // U_eff as operands, so it costs them no LDS reads but Q), else the io waves.
     // Register sets for the operands that come straight from global memory: two (two blocks of
     // loads in flight) where the registers allow, else one.
-    constexpr int kSets = (N <= 128 && !(D == 128 && N == 128 && C == 128 && TV == 32)) ? 2 : 1;
+    constexpr int kSets = (!GEN && N <= 128 && !(D == 128 && N == 128 && C == 128 && TV == 32)) ? 2 : 1;
     constexpr bool kStateReadout = RO && N <= 128;
     constexpr bool kIoReadout = RO && N > 128;
     static_assert(D % 64 == 0 && TV % 16 == 0 && N % 32 == 0, "tile shapes");
@@ -137,7 +143,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     Q += chain * (size_t)tail * D;
     K += chain * (size_t)tail * R * D;
     V += (size_t)vmul * chain * (size_t)tail * R * dv;
-    beta += chain * (size_t)tail * R;
+    beta += chain * (size_t)tail * R * (GEN ? D : 1);
     if (O) O += chain * (size_t)tail * dv;
 
     // ------------------------------------------------------------------ state waves
@@ -238,7 +244,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             r16 = lane & 15; g = lane >> 4;
             const size_t cid = c0 + ch;
             const size_t nx = ch + kSets < NC ? cid + kSets : c0 + NC - 1;   // the last steps re-fetch the last block
-            const bf16 *Kc = Ks + (kDoubleK ? (ch & 1) * N * KP : 0);
+            const bf16 *Kc = Ks + (kDoubleK ? (ch & 1) * KBUF : 0);
+            const bf16 *Ka = GEN ? Kc + N * KP : Kc;                 // rows that multiply the state: K, or A
 
             // Each interval first issues every LDS read it needs and only then starts its MFMAs
             // (LDS_FENCE keeps the reads from sinking down to their first use), so that the
@@ -254,14 +261,14 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 // start while the later operands are still on their way
 #pragma unroll
                 for (int ks = 0; ks < NKS; ++ks) {
-                    aK[0][ks] = ld8(&Kc[(16 * W + r16) * KP + 32 * ks + 8 * g]);
+                    aK[0][ks] = ld8(&Ka[(16 * W + r16) * KP + 32 * ks + 8 * g]);
 #pragma unroll
                     for (int nt = 0; nt < NNT; ++nt) bS[nt][ks] = ld8(&Sb[(16 * nt + r16) * SP + 32 * ks + 8 * g]);
                 }
 #pragma unroll
                 for (int i = 0; i < M1; ++i) {
                     const int mt = W + 4 * i;
-                    bt[i] = *reinterpret_cast<const f32x4 *>(&bs[16 * mt + 4 * g]);
+                    if constexpr (!GEN) bt[i] = *reinterpret_cast<const f32x4 *>(&bs[16 * mt + 4 * g]);
                     // V tile read transposed: 4 consecutive tokens of feature 16 nt + r16
 #pragma unroll
                     for (int nt = 0; nt < NNT; ++nt)
@@ -269,7 +276,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                     if (i + 1 < M1) {
 #pragma unroll
                         for (int ks = 0; ks < NKS; ++ks)
-                            aK[i + 1][ks] = ld8(&Kc[(16 * (W + 4 * (i + 1)) + r16) * KP + 32 * ks + 8 * g]);
+                            aK[i + 1][ks] = ld8(&Ka[(16 * (W + 4 * (i + 1)) + r16) * KP + 32 * ks + 8 * g]);
                     }
                 }
                 LDS_FENCE();
@@ -285,7 +292,9 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                         for (int nt = 0; nt < NNT; ++nt) acc[nt] = mfma16(aK[i][ks], bS[nt][ks], acc[nt]);
 #pragma unroll
                     for (int nt = 0; nt < NNT; ++nt) {
-                        f32x4 rr = (__builtin_convertvector(vt[i][nt], f32x4) - acc[nt]) * bt[i];
+                        f32x4 rr;
+                        if constexpr (GEN) rr = __builtin_convertvector(vt[i][nt], f32x4) + acc[nt];
+                        else rr = (__builtin_convertvector(vt[i][nt], f32x4) - acc[nt]) * bt[i];
                         st4(&Rs[(16 * nt + r16) * UP + 16 * mt + 4 * g], cvt4(rr));
                     }
                 }
@@ -430,7 +439,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
         // Two register sets, as in the state waves: block ch + 1 is staged into LDS during step ch
         // out of set (ch + 1) & 1, which is then refilled with block ch + 3, so that two blocks of K,
         // V tile and beta are on their way at any time.
-        bf16x8 kreg[kSets][KV], vreg[kSets][VV];
+        bf16x8 kreg[kSets][KV], vreg[kSets][VV], areg[kSets][GEN ? KV : 1];
         bf16 breg[kSets];
         bf16x8 p2[kSets][T2][NKT]; // P tiles of this wave's token tiles (those the causal mask keeps)
 
@@ -448,7 +457,10 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 #pragma unroll
             for (int q = 0; q < KV; ++q) {
                 const int v = tb + NTHR * q;
-                if (q >= q0 && q < q1 && ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8)) kreg[S][q] = ld8(Kg + (size_t)v * 8);
+                if (q >= q0 && q < q1 && ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8)) {
+                    kreg[S][q] = ld8(Kg + (size_t)v * 8);
+                    if constexpr (GEN) areg[S][q] = ld8(beta + cid * (size_t)N * D + (size_t)v * 8);
+                }
             }
         };
         auto fetch_vqb = [&](size_t cid, auto Sc) {
@@ -460,7 +472,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 v = v < N * PPR ? v : N * PPR - 1;                 // clamp instead of branching
                 vreg[S][q] = ld8(Vg + (size_t)(v / PPR) * dv + (v % PPR) * 8);
             }
-            breg[S] = beta[cid * (size_t)N + (tb % N)];
+            if constexpr (!GEN) breg[S] = beta[cid * (size_t)N + (tb % N)];
         };
         auto fetch_p = [&](size_t cid, auto Sc) {
             constexpr int S = decltype(Sc)::value % kSets;
@@ -489,8 +501,10 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 #pragma unroll
             for (int q = 0; q < KV; ++q) {
                 const int v = tb + NTHR * q;
-                if (q >= q0 && q < q1 && ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8))
+                if (q >= q0 && q < q1 && ((q + 1) * NTHR <= N * D / 8 || v < N * D / 8)) {
                     st8(&Kd[(v / VPR) * KP + (v % VPR) * 8], kreg[S][q]);
+                    if constexpr (GEN) st8(&Kd[N * KP + (v / VPR) * KP + (v % VPR) * 8], areg[S][q]);
+                }
             }
         };
         auto stage_vqb = [&](auto Sc) {
@@ -500,7 +514,9 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 const int v = tb + NTHR * q;
                 if (v < N * PPR) st8(&Vs[(v / PPR) * VP + (v % PPR) * 8], vreg[S][q]);
             }
-            if (tb < N) bs[tb] = (float)breg[S];
+            if constexpr (!GEN) {
+                if (tb < N) bs[tb] = (float)breg[S];
+            }
         };
         // the O tile of one chunk (chunk tokens x TV features), LDS -> its rows of O
         auto copy_out = [&](size_t cid) {
@@ -574,7 +590,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
                 }
                 fetch_q(n2, Pc);
             }
-            bf16 *Knext = Ks + (kDoubleK ? ((ch + 1) & 1) * N * KP : 0);
+            bf16 *Knext = Ks + (kDoubleK ? ((ch + 1) & 1) * KBUF : 0);
             if (kDoubleK) {
                 stage_k(Knext, 0, KH, Nc);
                 fetch_k(n3, 0, KH, Nc);
@@ -650,13 +666,13 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     X(64, 64, 64) X(64, 128, 32) X(64, 128, 64) X(64, 128, 128) X(64, 256, 64) X(64, 256, 128) \
     X(128, 64, 64) X(128, 128, 32) X(128, 128, 64) X(128, 128, 128) X(128, 256, 64) X(128, 256, 128)
 
-template <int D, int N, int C, int TV, bool RO>
+template <int D, int N, int C, int TV, bool RO, bool GEN = false>
 static hipError_t launch_scan_ro(const void *Q, const void *K, const void *V, const void *beta,
                                        const void *Tt, const void *Pt, const float *S0, void *O, float *SL,
                                        int heads, int NC, int tail, int vmul, int s0mul, int dv, hipStream_t stream)
 {
-    auto kern = scan_kernel<D, N, C, TV, RO>;
-    constexpr size_t lds = ScanLds<D, N, C, TV>::total;
+    auto kern = scan_kernel<D, N, C, TV, RO, GEN>;
+    constexpr size_t lds = ScanLds<D, N, C, TV, GEN>::total;
     static_assert(lds <= kMaxLdsBytes, "scan kernel LDS plan exceeds the CU");
     static std::atomic<uint64_t> armed{0};
     hipError_t e = arm_dynamic_lds(armed, reinterpret_cast<const void *>(kern), lds);
@@ -701,6 +717,28 @@ hipError_t launch_chunk_scan(const void *Q, const void *K, const void *V, const 
                 return launch_scan_instance<DD, NN, CC, 32>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, dv, stream); \
         }                                                                                                   \
         return launch_scan_instance<DD, NN, CC, 16>(Q, K, V, beta, Tt, Pt, S0, O, SL, heads, NC, tail, vmul, s0mul, dv, stream);   \
+    }
+    PF_SCAN_INSTANCES(X)
+#undef X
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_chunk_scan_general(const void *Q, const void *A, const void *Atil, const void *Bm, const void *Tt,
+                                     const void *Pt, const float *S0, void *O, float *SL, int heads, int L, int d,
+                                     int dv, int r, int chunk, hipStream_t stream)
+{
+    const int NC = L / chunk, tail = L % chunk;   // the tail tokens of every head are skipped
+    const int n = chunk * r;
+    if (!O || dv <= 0 || dv % 16 != 0 || (long long)heads * (dv / 16) > 0x7fffffffLL) return hipErrorInvalidValue;
+    const bool wide = scan_dv_tile(heads, dv, n) == 32;
+    // operand slots of the kernel: K <- B rows, beta <- A rows, V <- Atil rows
+#define X(DD, NN, CC)                                                                                      \
+    if constexpr (NN <= 128) {                                                                              \
+        if (d == DD && n == NN && chunk == CC) {                                                            \
+            if (wide)                                                                                       \
+                return launch_scan_ro<DD, NN, CC, 32, true, true>(Q, Bm, Atil, A, Tt, Pt, S0, O, SL, heads, NC, tail, 1, 1, dv, stream); \
+            return launch_scan_ro<DD, NN, CC, 16, true, true>(Q, Bm, Atil, A, Tt, Pt, S0, O, SL, heads, NC, tail, 1, 1, dv, stream);     \
+        }                                                                                                   \
     }
     PF_SCAN_INSTANCES(X)
 #undef X

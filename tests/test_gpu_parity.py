@@ -326,6 +326,79 @@ def test_general_driver_entry(pf, oracle, kw):
 
 
 # ---------------------------------------------------------------- launch-shape edge cases
+@pytest.mark.parametrize("kw", [
+    dict(N=3, L=256, r=2, dk=128, dv=128, C=64),
+    dict(N=2, L=256, r=1, dk=64, dv=64, C=64),
+    dict(N=2, L=160, r=4, dk=128, dv=64, C=32),             # d_v != d_k
+    dict(N=2, L=229, r=2, dk=64, dv=128, C=128),            # chunk 128 -> blocks of 64; ragged tail (generic kernel)
+    dict(N=64, L=128, r=2, dk=128, dv=128, C=64),           # 64 heads: 32-row d_v tiles, single-buffered operands
+    dict(N=2, L=192, r=1, dk=128, dv=32, C=128),            # 128 virtual tokens in blocks of 128 tokens
+    dict(N=2, L=40, r=2, dk=128, dv=128, C=64),             # shorter than one block: generic kernel alone
+])
+def test_general_drivers_on_mfma_kernels(pf, oracle, kw):
+    """pf_flow_fwd_mfma against the oracle's general-driver recurrence.  Drivers near the delta form
+    (so that the state stays bounded over hundreds of tokens) but with A and B independent of each
+    other, hence a non-symmetric system matrix; non-zero, non-symmetric S0."""
+    import torch
+    N, L, r, dk, dv, C = (kw[k] for k in ("N", "L", "r", "dk", "dv", "C"))
+    _say(f"[case] general drivers on the MFMA kernels {kw}")
+    rng = np.random.default_rng(91)
+    unit = lambda x: x / np.linalg.norm(x, axis=-1, keepdims=True)
+    k = unit(rng.standard_normal((N, L, r, dk)))
+    beta = 1.0 / (1.0 + np.exp(-rng.standard_normal((N, L, r, 1))))
+    A = (beta * (k + 0.3 * unit(rng.standard_normal(k.shape)))).astype(np.float32)
+    Bm = (-(k + 0.3 * unit(rng.standard_normal(k.shape)))).astype(np.float32)
+    At = (rng.standard_normal((N, L, r, dv)) / np.sqrt(dv)).astype(np.float32)
+    Q = (rng.standard_normal((N, L, dk)) / np.sqrt(dk)).astype(np.float32)
+    S0 = (0.1 * rng.standard_normal((N, dv, dk))).astype(np.float32)
+    dev = torch.device("cuda:0")
+    up = lambda a: torch.from_numpy(a).to(dev).to(torch.bfloat16).reshape((1, N) + a.shape[1:]).contiguous()
+    tq, ta, tat, tb = up(Q), up(A), up(At), up(Bm)
+    ts0 = torch.from_numpy(S0).to(dev).reshape(1, N, dv, dk).contiguous()
+    blk = pf.pf_flow_fwd_mfma_block(dk, dv, r, C, pf.PF_BF16)
+    assert 0 < blk <= C and blk * r <= 128
+    need = pf.pf_flow_fwd_mfma_workspace_bytes(1, N, L, dk, dv, r, C, pf.PF_BF16)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    O = torch.full((1, N, L, dv), float("nan"), dtype=torch.bfloat16, device=dev)
+    SL = torch.full((1, N, dv, dk), float("nan"), dtype=torch.float32, device=dev)
+    st = pf.pf_flow_fwd_mfma(tq, ta, tat, tb, ts0, O, SL, 1, N, L, dk, dv, r, C, pf.PF_BF16, ws, need)
+    assert st == pf.PF_OK, pf.pf_status_str(st)
+    torch.cuda.synchronize()
+    On, Sn = O.float().cpu().numpy()[0], SL.cpu().numpy()[0]
+    assert np.isfinite(On).all() and np.isfinite(Sn).all()
+    back = lambda t: t.float().cpu().numpy()[0].astype(np.float64)      # the values the GPU saw
+    heads = range(N) if N <= 4 else (0, N // 2, N - 1)
+    Oref, Sref = [], []
+    for h in heads:
+        o, sl = oracle.flow_head(back(ta)[h], back(tat)[h], back(tb)[h], back(tq)[h], S0[h].astype(np.float64))
+        Oref.append(o)
+        Sref.append(sl)
+    idx = list(heads)
+    assert_parity(output_stats(On[idx], np.stack(Oref)), state_errors(Sn[idx], np.stack(Sref)), "bf16")
+    # and the generic kernel (pf_flow_fwd) computes the same thing
+    O2, S2 = pf.flow_fwd(tq, ta, tat, tb, ts0, chunk=C)
+    torch.cuda.synchronize()
+    assert rel_l2(On, O2.float().cpu().numpy()[0]) <= 1e-2 and rel_l2(Sn, S2.cpu().numpy()[0]) <= 1e-2
+
+
+def test_general_drivers_mfma_argument_checks(pf):
+    import torch
+    BF = pf.PF_BF16
+    assert pf.pf_flow_fwd_mfma_block(128, 128, 2, 64, BF) == 64
+    assert pf.pf_flow_fwd_mfma_block(128, 128, 2, 128, BF) == 64          # 256 virtual tokens -> two blocks
+    assert pf.pf_flow_fwd_mfma_block(128, 128, 4, 64, BF) == 32
+    assert pf.pf_flow_fwd_mfma_block(128, 128, 8, 64, BF) == 0            # r = 8: no instance
+    assert pf.pf_flow_fwd_mfma_block(128, 128, 2, 64, pf.PF_F32) == 0
+    assert pf.pf_flow_fwd_mfma_block(96, 96, 1, 64, BF) == 0
+    t = torch.zeros(1 << 16, dtype=torch.bfloat16, device="cuda:0")
+    f = torch.zeros(1 << 16, dtype=torch.float32, device="cuda:0")
+    call = lambda *a: pf.pf_flow_fwd_mfma(t, t, t, t, None, t, f, *a)
+    assert call(1, 1, 64, 128, 128, 8, 64, BF, t, 1 << 17) == pf.PF_ERR_UNSUPPORTED
+    assert call(1, 1, 64, 128, 128, 2, 64, BF, None, 0) == pf.PF_ERR_WORKSPACE
+    assert call(1, 1, 64, 128, 128, 2, 64, BF, t, 16) == pf.PF_ERR_WORKSPACE
+    assert pf.pf_flow_fwd_mfma(None, t, t, t, None, t, f, 1, 1, 64, 128, 128, 2, 64, BF, t, 1 << 17) == pf.PF_ERR_NULL
+
+
 def test_more_workgroups_than_the_gpu_holds(pf, oracle):
     """640 heads x 4 d_v tiles = 2560 scan workgroups (ten per CU): workgroups are independent, so
     a grid far beyond what is resident at once must give the same per-head results."""
