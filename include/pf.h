@@ -98,8 +98,10 @@ size_t pf_delta_fwd_workspace_bytes(int B, int H, int L, int d_k, int d_v, int r
 /* Which kernels one pf_delta_fwd (or pf_delta_product_fwd) call with these dimensions enqueues, in
  * launch order: the names of the kernel instantiations as a profiler prints them (template
  * arguments included, parameter lists left out), separated by ';', e.g.
- * "pf::flow_kernel<128, 128, 64>;pf::scan_kernel<128, 128, 64, 32, true>".  The scan kernel's last
- * two arguments are the d_v rows one workgroup owns and whether it reads out O.  At most cap - 1
+ * "pf::flow_kernel<128, 64, 32, false>;pf::scan_kernel<128, 64, 32, 32, true, false>".  Template
+ * arguments: d_k, virtual tokens per block, tokens per block; for the scan kernel then the d_v rows
+ * one workgroup owns and whether it reads out O; last, whether the instance is the one for general
+ * drivers.  At most cap - 1
  * characters and a terminating NUL are written to buf (buf may be NULL); the return value is the
  * length of the whole description (0 for unsupported or invalid dimensions).  Depends on the
  * compute-unit count of the current device where the d_v tile does (256 when no device answers).

@@ -86,23 +86,27 @@ int tail_chunk(int d, int dv, int r)
 }
 
 // Tokens per flow block on the MFMA path: the requested chunk or chunk / 2^j (the flow over a
-// chunk is the composition of the flows over its pieces, Section 3.1).  Blocks of at most 128
-// virtual tokens are preferred where an instance exists: the hand-over array T grows with the
-// square of the block, and every d_v tile of a head reads all of it (measured on 32 heads x 65536
-// tokens, r = 2: 2.45 ms with blocks of 64 tokens against 3.31 ms with blocks of 128).  Else the
-// largest block that has an instance.  0 when no instance serves these dimensions.
+// chunk is the composition of the flows over its pieces, Section 3.1).  Small blocks are preferred
+// where an instance exists: the hand-over array T grows with the square of the block and every d_v
+// tile of a head reads all of it.  Measured (ms per forward; 64 / 128 / 256 virtual tokens per
+// block): 64 heads x 4096 tokens, r = 2: 0.201 / 0.224 / -; 32 heads x 65536 tokens, r = 2:
+// 2.31 / 2.39 / 3.27; r = 1, d = 64: 0.039 / 0.042 / -.  Blocks of fewer than 32 tokens lose again
+// (r = 4: 16 tokens 0.542, 32 tokens 0.529, 64 tokens 0.752).  So: 64 virtual tokens if that is
+// at least 32 tokens, else at most 128 virtual tokens, else the largest block that has an
+// instance.  0 when no instance serves these dimensions.
 int mfma_block(int d_k, int d_v, int r, int chunk, pf_dtype dt)
 {
     if (dt != PF_BF16 || d_v % 16 != 0) return 0;   // d_k: where an instance exists (64, 128)
-    int any = 0;
+    int any = 0, upto128 = 0;
     for (int c = chunk; c >= 16; c /= 2) {
         if ((long long)c * r <= 4096 && pf::mfma_instance_exists(d_k, c * r, c)) {
-            if (c * r <= 128) return c;
+            if (c * r == 64 && c >= 32) return c;
+            if (c * r <= 128 && !upto128) upto128 = c;
             if (!any) any = c;
         }
         if (c % 2 != 0) break;
     }
-    return any;
+    return upto128 ? upto128 : any;
 }
 
 // The same choice for the general drivers: blocks of at most 128 virtual tokens only.
@@ -235,14 +239,14 @@ size_t pf_delta_fwd_describe(int B, int H, int L, int d_k, int d_v, int r, int c
             const int heads = B * H, n = block * r;
             const int G = scan_segments(heads, L, d_k, d_v, r, block);
             const std::string dims = std::to_string(d_k) + ", " + std::to_string(n) + ", " + std::to_string(block);
-            const std::string flow = "pf::flow_kernel<" + dims + ">";
+            const std::string flow = "pf::flow_kernel<" + dims + ", false>";
             const std::string scan = "pf::scan_kernel<" + dims + ", " +
                                      std::to_string(pf::scan_dv_tile(heads * G, d_v, n));
             if (G > 1)
-                out = flow + ";pf::segment_constants_kernel;" + scan + ", false>;" + scan + ", false>;" +
-                      "pf::segment_compose_kernel;" + scan + ", true>";
+                out = flow + ";pf::segment_constants_kernel;" + scan + ", false, false>;" + scan + ", false, false>;" +
+                      "pf::segment_compose_kernel;" + scan + ", true, false>";
             else
-                out = flow + ";" + scan + ", true>";
+                out = flow + ";" + scan + ", true, false>";
             if (tail) out += ";" + generic;
         }
     }

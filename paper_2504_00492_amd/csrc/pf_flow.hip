@@ -380,8 +380,8 @@ __global__ __launch_bounds__(kFlowThreads) void flow_kernel(
 
 // ---------------------------------------------------------------------------- host side
 #define PF_FLOW_INSTANCES(X) \
-    X(64, 64, 64) X(64, 128, 32) X(64, 128, 64) X(64, 128, 128) X(64, 256, 64) X(64, 256, 128) \
-    X(128, 64, 64) X(128, 128, 32) X(128, 128, 64) X(128, 128, 128) X(128, 256, 64) X(128, 256, 128)
+    X(64, 64, 64) X(64, 64, 32) X(64, 128, 32) X(64, 128, 64) X(64, 128, 128) X(64, 256, 64) X(64, 256, 128) \
+    X(128, 64, 64) X(128, 64, 32) X(128, 128, 32) X(128, 128, 64) X(128, 128, 128) X(128, 256, 64) X(128, 256, 128)
 
 bool mfma_instance_exists(int d, int n, int chunk)
 {

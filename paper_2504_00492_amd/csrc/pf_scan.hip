@@ -110,6 +110,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     // U_eff as operands, so it costs them no LDS reads but Q), else the io waves.
     // Register sets for the operands that come straight from global memory: two (two blocks of
     // loads in flight) where the registers allow, else one.
+    // (measured on blocks of 64 virtual tokens, 64 heads x 4096 / 32 heads x 65536 tokens: one set
+    // 0.144 / 1.90 ms, two sets 0.136 / 1.79 ms, four sets 0.142 / 2.07 ms)
     constexpr int kSets = (!GEN && N <= 128 && !(D == 128 && N == 128 && C == 128 && TV == 32)) ? 2 : 1;
     constexpr bool kStateReadout = RO && N <= 128;
     constexpr bool kIoReadout = RO && N > 128;
@@ -663,8 +665,8 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 
 // ---------------------------------------------------------------------------- host side
 #define PF_SCAN_INSTANCES(X) \
-    X(64, 64, 64) X(64, 128, 32) X(64, 128, 64) X(64, 128, 128) X(64, 256, 64) X(64, 256, 128) \
-    X(128, 64, 64) X(128, 128, 32) X(128, 128, 64) X(128, 128, 128) X(128, 256, 64) X(128, 256, 128)
+    X(64, 64, 64) X(64, 64, 32) X(64, 128, 32) X(64, 128, 64) X(64, 128, 128) X(64, 256, 64) X(64, 256, 128) \
+    X(128, 64, 64) X(128, 64, 32) X(128, 128, 32) X(128, 128, 64) X(128, 128, 128) X(128, 256, 64) X(128, 256, 128)
 
 template <int D, int N, int C, int TV, bool RO, bool GEN = false>
 static hipError_t launch_scan_ro(const void *Q, const void *K, const void *V, const void *beta,

@@ -43,14 +43,16 @@ def test_version_and_status_strings(pf):
 
 def test_flow_block(pf):
     F32, BF = pf.PF_F32, pf.PF_BF16
-    assert pf.pf_delta_fwd_block(128, 128, 2, 64, BF) == 64
-    assert pf.pf_delta_fwd_block(128, 128, 2, 128, BF) == 64            # 256 virtual tokens -> 2 x 128
-    assert pf.pf_delta_fwd_block(128, 128, 4, 128, BF) == 32            # 512 virtual tokens -> 4 x 128
+    assert pf.pf_delta_fwd_block(128, 128, 2, 64, BF) == 32             # 64 virtual tokens preferred (>= 32 tokens)
+    assert pf.pf_delta_fwd_block(128, 128, 2, 128, BF) == 32            # 256 virtual tokens -> 4 x 64
+    assert pf.pf_delta_fwd_block(128, 128, 4, 128, BF) == 32            # r = 4: 64 virtual tokens would be 16 tokens -> 128
     assert pf.pf_delta_fwd_block(128, 128, 4, 64, BF) == 32
-    assert pf.pf_delta_fwd_block(128, 128, 1, 128, BF) == 128           # 128 virtual tokens as they are
+    assert pf.pf_delta_fwd_block(128, 128, 1, 128, BF) == 64            # r = 1: blocks of 64 tokens
+    assert pf.pf_delta_fwd_block(128, 128, 1, 32, BF) == 0 or pf.pf_delta_fwd_supported(128, 128, 1, 32, BF) == 1   # no 32-token r = 1 instance
     assert pf.pf_delta_fwd_block(128, 128, 8, 64, BF) == 4              # no MFMA instance for r = 8: generic path, 4 tokens
     assert pf.pf_delta_fwd_block(128, 128, 8, 32, BF) == 4              # (256, 32) has no instance, 16 x 8 neither
-    assert pf.pf_delta_fwd_block(64, 64, 1, 512, BF) == 128
+    assert pf.pf_delta_fwd_block(64, 64, 1, 512, BF) == 64
+    assert pf.pf_delta_fwd_block(64, 64, 2, 64, BF) == 32
     assert pf.pf_delta_fwd_block(16, 16, 1, 16, F32) == 16             # generic path: the chunk itself
     # workspace follows the block, not the requested chunk
     assert (pf.pf_delta_fwd_workspace_bytes(2, 16, 8192, 128, 128, 4, 128, BF)
@@ -61,7 +63,7 @@ def test_flow_block(pf):
     assert pf.pf_delta_chunk_supported(128, 64, 1, 64) == 1 and pf.pf_delta_chunk_supported(96, 96, 1, 64) == 0
     fake = 0x1000
     assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 256, 128, 128, 4, 128, 0) == pf.PF_ERR_UNSUPPORTED
-    assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 256, 128, 128, 2, 32, 0) == pf.PF_ERR_UNSUPPORTED
+    assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 256, 128, 128, 2, 16, 0) == pf.PF_ERR_UNSUPPORTED
     assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 100, 128, 128, 4, 32, 0) == pf.PF_ERR_SHAPE
     assert pf.pf_delta_chunk_flow(fake, fake, fake, fake, fake, 1, 1, 100, 128, 128, 2, 128, 0) == pf.PF_ERR_SHAPE
 
@@ -70,12 +72,14 @@ def test_describe_names_the_kernels_a_call_launches(pf):
     BF, F32 = pf.PF_BF16, pf.PF_F32
     # (the d_v tile depends on the compute-unit count: 256 is assumed when no device answers)
     assert pf.pf_delta_fwd_describe(4, 16, 4096, 128, 128, 2, 64, BF) == [
-        "pf::flow_kernel<128, 128, 64>", "pf::scan_kernel<128, 128, 64, 32, true>"]
-    assert pf.pf_delta_fwd_describe(1, 32, 65536, 128, 128, 2, 128, BF) == [           # chunk 128 -> blocks of 64
-        "pf::flow_kernel<128, 128, 64>", "pf::scan_kernel<128, 128, 64, 16, true>"]
+        "pf::flow_kernel<128, 64, 32, false>", "pf::scan_kernel<128, 64, 32, 32, true, false>"]
+    assert pf.pf_delta_fwd_describe(1, 32, 65536, 128, 128, 2, 128, BF) == [           # chunk 128 -> blocks of 32
+        "pf::flow_kernel<128, 64, 32, false>", "pf::scan_kernel<128, 64, 32, 16, true, false>"]
+    assert pf.pf_delta_fwd_describe(2, 16, 8192, 128, 128, 4, 64, BF) == [
+        "pf::flow_kernel<128, 128, 32, false>", "pf::scan_kernel<128, 128, 32, 16, true, false>"]
     seg = pf.pf_delta_fwd_describe(1, 4, 65536, 128, 128, 2, 64, BF)                    # few heads: segments
-    assert seg[0] == "pf::flow_kernel<128, 128, 64>" and seg[-1] == "pf::scan_kernel<128, 128, 64, 16, true>"
-    assert seg.count("pf::scan_kernel<128, 128, 64, 16, false>") == 2 and "pf::segment_compose_kernel" in seg
+    assert seg[0] == "pf::flow_kernel<128, 64, 32, false>" and seg[-1] == "pf::scan_kernel<128, 64, 32, 16, true, false>"
+    assert seg.count("pf::scan_kernel<128, 64, 32, 16, false, false>") == 2 and "pf::segment_compose_kernel" in seg
     assert pf.pf_delta_fwd_describe(1, 4, 100, 128, 128, 2, 64, BF)[-1] == "pf::generic_kernel<unsigned short, false>"
     assert pf.pf_delta_fwd_describe(1, 1, 64, 16, 16, 1, 16, F32) == ["pf::generic_kernel<float, false>"]
     assert pf.pf_delta_fwd_describe(1, 1, 64, 256, 256, 1, 16, F32) == []               # unsupported
@@ -85,7 +89,7 @@ def test_describe_names_the_kernels_a_call_launches(pf):
     from paper_2504_00492_amd.binding import _lib
     buf = ctypes.create_string_buffer(8)
     n = _lib.pf_delta_fwd_describe(4, 16, 4096, 128, 128, 2, 64, BF, buf, 8)
-    assert n == len("pf::flow_kernel<128, 128, 64>;pf::scan_kernel<128, 128, 64, 32, true>") and buf.value == b"pf::flo"
+    assert n == len("pf::flow_kernel<128, 64, 32, false>;pf::scan_kernel<128, 64, 32, 32, true, false>") and buf.value == b"pf::flo"
 
 
 def test_static_entry_host_checks(pf):
@@ -141,24 +145,24 @@ def test_workspace_bytes(pf):
     assert pf.pf_delta_fwd_workspace_bytes(1, 1, 64, 16, 16, 1, 16, pf.PF_F32) == 0
     b = pf.pf_delta_fwd_workspace_bytes(4, 16, 4096, 128, 128, 2, 64, BF)
     tok = 4 * 16 * 4096
-    assert b >= tok // 64 * 128 * 128 * 2 + tok * 128 * 2 and b % 256 == 0
+    assert b >= tok // 32 * 64 * 64 * 2 + tok * 64 * 2 and b % 256 == 0           # blocks of 32 tokens, n = 64
     # a ragged tail adds the state hand-over buffer to the whole blocks' scratch
     assert pf.pf_delta_fwd_workspace_bytes(4, 16, 4097, 128, 128, 2, 64, BF) == b + 4 * 16 * 128 * 128 * 4
-    assert pf.pf_delta_fwd_workspace_bytes(4, 16, 63, 128, 128, 2, 64, BF) == 0       # shorter than one block
+    assert pf.pf_delta_fwd_workspace_bytes(4, 16, 31, 128, 128, 2, 64, BF) == 0       # shorter than one block
     assert pf.pf_delta_fwd_workspace_bytes(0, 16, 4096, 128, 128, 2, 64, BF) == 0
 
 
 def test_workspace_of_the_segment_parallel_scan(pf):
     """Few heads, long sequence: 3 d x d fp32 matrices per segment plus the two constants."""
     BF = pf.PF_BF16
-    d, r, C, L = 128, 2, 64, 65536
+    d, r, C, L = 128, 2, 32, 65536        # (chunk 64 runs as blocks of 32 tokens as well)
     n = C * r
     plain = lambda heads: heads * (L // C) * (n * n + C * n) * 2
     b4 = pf.pf_delta_fwd_workspace_bytes(1, 4, L, d, d, r, C, BF)         # 32 chains -> 8 segments
     assert b4 == plain(4) + n * d * 2 + d * d * 4 + 3 * 4 * 8 * d * d * 4
     b8 = pf.pf_delta_fwd_workspace_bytes(1, 8, L, d, d, r, C, BF)         # 64 chains: plain scan
     assert b8 == plain(8)
-    assert pf.pf_delta_fwd_workspace_bytes(1, 4, 1024, d, d, r, C, BF) == plain(4) * 1024 // L   # too short to cut
+    assert pf.pf_delta_fwd_workspace_bytes(1, 4, 512, d, d, r, C, BF) == plain(4) * 512 // L   # too short to cut
 
 
 def test_argument_checks_return_before_launch(pf):
