@@ -384,8 +384,8 @@ def test_general_drivers_on_mfma_kernels(pf, oracle, kw):
 def test_general_drivers_mfma_argument_checks(pf):
     import torch
     BF = pf.PF_BF16
-    assert pf.pf_flow_fwd_mfma_block(128, 128, 2, 64, BF) == 64
-    assert pf.pf_flow_fwd_mfma_block(128, 128, 2, 128, BF) == 64          # 256 virtual tokens -> two blocks
+    assert pf.pf_flow_fwd_mfma_block(128, 128, 2, 64, BF) == 32           # 64 virtual tokens preferred
+    assert pf.pf_flow_fwd_mfma_block(128, 128, 2, 128, BF) == 32
     assert pf.pf_flow_fwd_mfma_block(128, 128, 4, 64, BF) == 32
     assert pf.pf_flow_fwd_mfma_block(128, 128, 8, 64, BF) == 0            # r = 8: no instance
     assert pf.pf_flow_fwd_mfma_block(128, 128, 2, 64, pf.PF_F32) == 0
