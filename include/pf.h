@@ -80,14 +80,15 @@ const char *pf_status_str(pf_status s);
  */
 int pf_delta_fwd_supported(int d_k, int d_v, int r, int chunk, pf_dtype dt);
 
-/* Tokens per flow block actually used for these dimensions.  MFMA path: chunk / 2^j for the smallest j
- * (j = 0 included) whose block has a kernel instance and at most 128 virtual tokens (block * r);
- * failing that, for the smallest j whose block has an instance at all (256 virtual tokens).
- * Smaller blocks are preferred because the per-block hand-over array grows with the square of the
- * block.  The flow over a chunk is the composition of the flows over consecutive pieces of it
- * (Section 3.1), so O and S_L are the same function of the inputs either way; only the blocking of
- * the arithmetic, hence its rounding, differs.  On the generic path: the requested chunk, halved
- * until its working set fits LDS.  0 when pf_delta_fwd_supported(...) is 0.  Host only. */
+/* Tokens per flow block actually used for these dimensions.  MFMA path: chunk / 2^j (j = 0 included)
+ * among the blocks that have a kernel instance: the one of 64 virtual tokens (block * r) if it holds at
+ * least 32 tokens; else the largest of at most 128 virtual tokens; else the largest there is (256
+ * virtual tokens).  Small blocks are preferred because the per-block hand-over array grows with the
+ * square of the block; below 32 tokens the fixed cost of a block outweighs that.  The flow over a chunk
+ * is the composition of the flows over consecutive pieces of it (Section 3.1), so O and S_L are the
+ * same function of the inputs either way; only the blocking of the arithmetic, hence its rounding,
+ * differs.  On the generic path: the requested chunk, halved until its working set fits LDS.  0 when
+ * pf_delta_fwd_supported(...) is 0.  Host only. */
 int pf_delta_fwd_block(int d_k, int d_v, int r, int chunk, pf_dtype dt);
 
 /* Bytes of device scratch pf_delta_fwd needs for these dimensions (0 for the generic path, for
@@ -237,8 +238,8 @@ pf_status pf_flow_fwd(const void *Q, const void *A, const void *Atil, const void
  *   U_eff = T (Atil + A S_c^T),   O_c = Q S_c^T + P U_eff,   S_c+1 = S_c + U_eff^T B .
  *
  * d_k in {64, 128}, d_v a multiple of 16, flow blocks of at most 128 virtual tokens:
- * pf_flow_fwd_mfma_block returns the block used (chunk / 2^j for the smallest j with block * r <= 128
- * and a kernel instance), 0 when none exists (then PF_ERR_UNSUPPORTED: use pf_flow_fwd).  Any L: the
+ * pf_flow_fwd_mfma_block returns the block used (chosen as for pf_delta_fwd_block, among blocks with
+ * block * r <= 128), 0 when none exists (then PF_ERR_UNSUPPORTED: use pf_flow_fwd).  Any L: the
  * L % block tokens at the end of every (b, h) go through the generic kernel.  workspace: at least
  * pf_flow_fwd_mfma_workspace_bytes(...) bytes of device scratch, overwritten.  Arguments otherwise as
  * pf_flow_fwd, errors as pf_delta_fwd.
