@@ -81,3 +81,41 @@ def test_static_scratch_limit_and_checks(pf):
     O2, S2 = pf.delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], None, chunk=16)
     torch.cuda.synchronize()
     assert torch.equal(O, O2) and torch.equal(S, S2)
+
+
+def test_static_scratch_call_inside_a_graph(pf):
+    """What the entry point is for: recorded into a HIP graph (no allocation may happen there).
+    Every replay, with eager calls on the same static buffer in between, reproduces the eager
+    result bit for bit.  (pf_init and one eager call come first: the buffer's address and the
+    kernels' LDS opt-ins are looked up outside the capture.)"""
+    import torch
+    assert pf.pf_init() == pf.PF_OK
+    w = synth.WORKLOADS["cfg2"].with_(B=1, H=4, L=256, s0_std=0.1)
+    inp = synth.make_inputs(w)
+    dev = to_device(w, inp)
+    B, H, L, r, d = w.B, w.H, w.L, w.r, w.d_k
+    args = lambda O, S: (dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], O, S, B, H, L, d, d, r, w.chunk, pf.PF_BF16)
+    O_e = torch.empty(B, H, L, d, dtype=torch.bfloat16, device="cuda:0")
+    S_e = torch.empty(B, H, d, d, dtype=torch.float32, device="cuda:0")
+    assert pf.pf_delta_fwd_static(*args(O_e, S_e)) == pf.PF_OK
+    torch.cuda.synchronize()
+    O_g, S_g = torch.empty_like(O_e), torch.empty_like(S_e)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        st = pf.pf_delta_fwd_static(*args(O_g, S_g), torch.cuda.current_stream())
+        assert st == pf.PF_OK
+    small = synth.WORKLOADS["cfg1"].with_(B=1, H=2, L=128)
+    sdev = to_device(small, synth.make_inputs(small))
+    for rep in range(3):
+        O_g.fill_(float("nan"))
+        S_g.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O_g, O_e) and torch.equal(S_g, S_e), f"replay {rep}"
+        # an eager call of another shape on the same static buffer between the replays
+        Os = torch.empty(1, 2, 128, 64, dtype=torch.bfloat16, device="cuda:0")
+        Ss = torch.empty(1, 2, 64, 64, dtype=torch.float32, device="cuda:0")
+        assert pf.pf_delta_fwd_static(sdev["Q"], sdev["K"], sdev["V"], sdev["beta"], None, Os, Ss, 1, 2, 128, 64, 64, 1,
+                                      64, pf.PF_BF16) == pf.PF_OK
+        torch.cuda.synchronize()
