@@ -58,6 +58,12 @@ def flops_per_token_head(d, r, C):
     return 3 * d * r * r * (C - 1) + (4 * r + 2) * d * d + 2 * d * r * (C + 1)
 
 
+def dense_flops_per_token_head(d, r, C):
+    """What full-tile execution would run (no use of the triangular / causal structure):
+    6 C r^2 d + (4r+2) d^2 + 4 C r d.  Reported beside the headline, never as the headline."""
+    return 6 * C * r * r * d + (4 * r + 2) * d * d + 4 * C * r * d
+
+
 def kernel_flops_per_token_head(d, r, C):
     """Useful FLOPs each kernel executes per token-head (the explicit inverse of the n x n
     triangular system, about C^2 r^3 / 3, is not counted).
@@ -287,6 +293,9 @@ def run_workload(pf, torch, w, inputs, args, traffic_table):
         "config": {"workload": f"{w.name}: B={B} H={H} L={L} d_k=d_v={dk} r={r} chunk={C} {w.dtype}",
                    "kernel_family": {1: "generic", 2: "mfma"}[fam], "flow_block": block, "launches": launched},
         "alg_tflops": alg_tflops, "frac_bf16_mfma_peak": alg_tflops / PEAK_BF16_TFLOPS,
+        # the same time priced with the full-tile flop count of the blocking that ran (padding and
+        # masked-out products included): an upper bound on what the MFMA pipe executed, not a headline
+        "dense_tflops": dense_flops_per_token_head(dk, r, block) * token_heads / (ms_per_step * 1e-3) / 1e12,
         "token_heads_per_s": token_heads / (ms_per_step * 1e-3),
         "min_hbm_gbs": min_bytes / (ms_per_step * 1e-3) / 1e9,
         "frac_hbm_peak_min_traffic": min_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,

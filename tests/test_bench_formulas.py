@@ -48,3 +48,16 @@ def test_yardsticks(bench, d, r, C, f_alg, bytes_bf16):
 def test_config0_fp32_yardsticks(bench):
     assert bench.flops_per_token_head(16, 1, 16) == 2800
     assert bench.min_bytes_per_token_head(16, 1, 4) == 260
+
+
+@pytest.mark.parametrize("d,r,C,f_dense", [
+    (16, 1, 16, 4096),                # config 0
+    (64, 1, 64, 65536),               # config 1
+    (128, 2, 64, 425984),             # config 2
+    (128, 4, 64, 1212416),            # config 3, chunk 64
+    (128, 4, 128, 2129920),           # config 3, chunk 128
+    (128, 2, 128, 688128),            # config 4
+])
+def test_full_tile_count(bench, d, r, C, f_dense):
+    assert bench.dense_flops_per_token_head(d, r, C) == f_dense
+    assert bench.dense_flops_per_token_head(d, r, C) > bench.flops_per_token_head(d, r, C)
