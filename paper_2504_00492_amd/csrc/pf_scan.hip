@@ -113,6 +113,13 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     // (measured on blocks of 64 virtual tokens, 64 heads x 4096 / 32 heads x 65536 tokens: one set
     // 0.144 / 1.90 ms, two sets 0.136 / 1.79 ms, four sets 0.142 / 2.07 ms)
     constexpr int kSets = (!GEN && N <= 128 && !(D == 128 && N == 128 && C == 128 && TV == 32)) ? 2 : 1;
+    // Recomputing the per-lane offsets every step costs about 100 integer instructions per wave
+    // and step but keeps them out of the registers.  Where registers are plentiful (blocks of 64
+    // virtual tokens with 32-row tiles, or d = 64) hoisting them wins: 64 heads x 4096 tokens,
+    // d = 128: scan 0.130 against 0.136 ms; d = 64: 0.0276 against 0.0292 ms.  With 16-row tiles at
+    // d = 128 it loses (1.85 against 1.78 ms on 32 heads x 65536 tokens), with 128 virtual tokens
+    // per block too (0.410 against 0.398 ms), and the 32-row instances there would spill.
+    constexpr bool kLaunder = !(N <= 64 && (TV == 32 || D == 64));
     constexpr bool kStateReadout = RO && N <= 128;
     constexpr bool kIoReadout = RO && N > 128;
     static_assert(D % 64 == 0 && TV % 16 == 0 && N % 32 == 0, "tile shapes");
@@ -240,9 +247,9 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             constexpr int PS = decltype(Pc)::value % kSets;   // register set of this block
             // The lane id is laundered once per step so that the per-lane LDS offsets of the
             // unrolled code below are recomputed where they are used instead of being hoisted
-            // out of this loop and held in registers for the whole kernel.
+            // out of this loop and held in registers for the whole kernel (kLaunder, see below).
             lane = lane0;
-            asm volatile("" : "+v"(lane));
+            if constexpr (kLaunder) asm volatile("" : "+v"(lane));
             r16 = lane & 15; g = lane >> 4;
             const size_t cid = c0 + ch;
             const size_t nx = ch + kSets < NC ? cid + kSets : c0 + NC - 1;   // the last steps re-fetch the last block
@@ -563,7 +570,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
             constexpr int PS = decltype(Pc)::value % kSets;                          // set of block ch
             constexpr std::integral_constant<int, (decltype(Pc)::value + 1) % kSets> Nc{};   // set that holds block ch + 1
             tb = tb0;
-            asm volatile("" : "+v"(tb));
+            if constexpr (kLaunder) asm volatile("" : "+v"(tb));
             lane = tb & 63; r16 = lane & 15; g = lane >> 4;
             const size_t cid = c0 + ch;
             const size_t n2 = ch + kSets < NC ? cid + kSets : c0 + NC - 1;          // block to request into this block's set
@@ -664,9 +671,11 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
 }
 
 // ---------------------------------------------------------------------------- host side
+#ifndef PF_SCAN_INSTANCES
 #define PF_SCAN_INSTANCES(X) \
     X(64, 64, 64) X(64, 64, 32) X(64, 128, 32) X(64, 128, 64) X(64, 128, 128) X(64, 256, 64) X(64, 256, 128) \
     X(128, 64, 64) X(128, 64, 32) X(128, 128, 32) X(128, 128, 64) X(128, 128, 128) X(128, 256, 64) X(128, 256, 128)
+#endif
 
 template <int D, int N, int C, int TV, bool RO, bool GEN = false>
 static hipError_t launch_scan_ro(const void *Q, const void *K, const void *V, const void *beta,
