@@ -305,8 +305,8 @@ pf_status pf_delta_chunk_scan(const void *Q, const void *K, const void *V, const
  * block (T and P of Theorem 3.2) is built inside the workgroup that scans the block and never
  * leaves the compute unit, so there is no workspace, and device memory sees Q, K, V, beta once
  * and O once as long as the d_v tiles of a (b, h), which share K and Q through one L2, stay in
- * step (measured 1.01-1.03 times the minimal traffic at 2048 to 8192 tokens per head, 1.76
- * times at 65536 tokens, where the eight tiles of a head drift apart).  The price: every d_v
+ * step (measured 1.01-1.03 times the minimal traffic at 2048 to 8192 tokens per head, 1.4 to
+ * 1.8 times at 65536 tokens, where the eight tiles of a head drift apart).  The price: every d_v
  * tile of a (b, h) repeats the block's flow for itself, which on MI355X costs more time than
  * the workspace traffic it saves; pf_delta_fwd therefore uses the two kernels of
  * pf_delta_chunk_flow / pf_delta_chunk_scan and is the faster call wherever a workspace can be

@@ -38,8 +38,8 @@
 //
 // Measured on MI355X (d = 128, r = 2): 64 heads of 4096 tokens, 32-row tiles: 1.01 times the
 // minimal HBM bytes, 0.22 ms, the same time as the two-kernel path; 32 heads of 65536 tokens,
-// 16-row tiles: 1.76 times the minimal bytes (the eight tiles of a head drift apart over 1024
-// blocks and miss each other's K and Q in L2), 2.8 ms against 2.4 ms.  A compute unit does the
+// 16-row tiles: 1.4 to 1.8 times the minimal bytes (the eight tiles of a head drift apart over
+// 1024 blocks and miss each other's K and Q in L2), 2.8 ms against 2.3 ms.  A compute unit does the
 // flow of its block D / TV times over, and the chain, the Gram and the substitution all draw on
 // the same LDS ports (MFMA pipe busy 31 %, LDS 56 % of the cycles).  It serves callers that
 // have no workspace.
