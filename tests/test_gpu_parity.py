@@ -170,7 +170,9 @@ def test_mfma_other_instances(pf, oracle, d, r, C):
     dict(B=1, H=2, L=160, d_k=128, d_v=48, r=4, chunk=32),                 # d_v = 48: three 16-row tiles
     dict(B=4, H=8, L=128, d_k=64, d_v=256, r=2, chunk=64, s0_std=0.1),     # 32 heads x 8 tiles of 32 rows
     dict(B=1, H=2, L=229, d_k=128, d_v=64, r=2, chunk=64, s0_std=0.1),     # ragged tail through the generic kernel
-    dict(B=1, H=2, L=256, d_k=128, d_v=32, r=2, chunk=128),                # blocks of 256 virtual tokens -> 64 tokens
+    dict(B=1, H=2, L=256, d_k=128, d_v=32, r=2, chunk=128),                # chunk 128 -> blocks of 32 tokens
+    dict(B=1, H=3, L=128, d_k=64, d_v=16, r=1, chunk=64),                  # a single 16-row tile per head
+    dict(B=1, H=1, L=96, d_k=128, d_v=512, r=2, chunk=32, s0_std=0.1),     # d_v = 4 d_k: 32 tiles of one head
 ])
 def test_mfma_path_dv_differs_from_dk(pf, oracle, kw):
     """The state is d_v x d_k; only d_k is a compile-time size of the MFMA kernels."""
