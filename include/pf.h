@@ -71,8 +71,8 @@ const char *pf_status_str(pf_status s);
  *      pf_delta_fwd_block) with block * r in {64, 128, 256}, block in {32, 64, 128}.  Any L: the
  *      L % block tokens left over at the end of every (b, h) are taken by the generic kernel
  *      from the state the whole blocks leave behind (the flows compose, Section 3.1).
- *      With few (b, h) pairs and a long L (the plain scan would use at most an eighth of the
- *      GPU) and d_k = d_v, every head is cut into 8 or more segments that are scanned side by side: a
+ *      With few (b, h) pairs and a long L (the plain scan would use at most a quarter of the
+ *      GPU) and d_k = d_v, every head is cut into 4 or more segments that are scanned side by side: a
  *      segment acts on the state as S -> S P + H (Proposition 2.1), P and H of all segments are
  *      computed in parallel, composed per head, and the segments re-run from their true
  *      incoming states.  Same results up to rounding; the workspace grows by a few d x d

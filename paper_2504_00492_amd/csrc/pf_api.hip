@@ -38,18 +38,19 @@ struct WorkspacePlan {
 // Segments per head for the segment-parallel scan: 1 (plain hand-over chain per head) unless
 // the chains of the plain scan (heads x d_v tiles) would leave three quarters of the CUs idle
 // and there are enough blocks to cut.  Three passes of the scan kernel then run with
-// `segments` times as many chains; measured, eight segments pay (1.6-1.7x on 4 heads of 65536
-// tokens) and four only break even.
+// `segments` times as many chains.  Measured on 65536 tokens, d = 128, r = 2: eight segments
+// on 4 heads 0.96 ms against 1.75 ms, four segments on 8 heads 1.52 against 1.83 ms; two
+// segments (three passes over half the blocks each) cannot pay.
 int scan_segments(int heads, int L, int d, int dv, int r, int chunk)
 {
     if (L % chunk != 0 || d != dv) return 1;     // (the composition kernel takes square states)
     const int NC = L / chunk;
     const long long chains = (long long)heads * (d / pf::scan_dv_tile(heads, d, chunk * r));
     const int cus = pf::device_cu_count();
-    if (chains > cus / 8 || NC < 32) return 1;
+    if (chains > cus / 4 || NC < 32) return 1;
     int G = 1;
     while (2 * G * chains <= cus && NC % (2 * G) == 0 && NC / (2 * G) >= 4) G *= 2;
-    return G >= 8 ? G : 1;
+    return G >= 4 ? G : 1;
 }
 // L tokens per head of which the first L - L % chunk (whole flow blocks) go through the MFMA
 // kernels; when a tail remains, a state buffer carries S from them to the kernel of the tail.

@@ -160,8 +160,10 @@ def test_workspace_of_the_segment_parallel_scan(pf):
     plain = lambda heads: heads * (L // C) * (n * n + C * n) * 2
     b4 = pf.pf_delta_fwd_workspace_bytes(1, 4, L, d, d, r, C, BF)         # 32 chains -> 8 segments
     assert b4 == plain(4) + n * d * 2 + d * d * 4 + 3 * 4 * 8 * d * d * 4
-    b8 = pf.pf_delta_fwd_workspace_bytes(1, 8, L, d, d, r, C, BF)         # 64 chains: plain scan
-    assert b8 == plain(8)
+    b8 = pf.pf_delta_fwd_workspace_bytes(1, 8, L, d, d, r, C, BF)         # 64 chains -> 4 segments
+    assert b8 == plain(8) + n * d * 2 + d * d * 4 + 3 * 8 * 4 * d * d * 4
+    b16 = pf.pf_delta_fwd_workspace_bytes(1, 16, L, d, d, r, C, BF)       # 128 chains: plain scan
+    assert b16 == plain(16)
     assert pf.pf_delta_fwd_workspace_bytes(1, 4, 512, d, d, r, C, BF) == plain(4) * 512 // L   # too short to cut
 
 

@@ -504,7 +504,8 @@ def test_calls_can_be_captured_in_a_graph(pf):
 @pytest.mark.parametrize("name,kw", [
     ("cfg2", dict(B=1, H=2, L=4096)),                 # 16 chains -> 16 segments per head
     ("cfg1", dict(B=1, H=1, L=2048, s0_std=0.2)),     # d = 64, one head, nonzero S0
-    ("cfg4", dict(B=1, H=3, L=4096, s0_std=0.1)),     # n = 256 instance, near-reflection betas
+    ("cfg4", dict(B=1, H=3, L=4096, s0_std=0.1)),     # chunk 128, near-reflection betas
+    ("cfg2", dict(B=1, H=8, L=4096, s0_std=0.1)),     # 64 chains -> 4 segments per head
 ])
 def test_segment_parallel_scan(pf, oracle, name, kw):
     """Few heads and a long sequence: the library cuts every head into segments that run as
