@@ -501,6 +501,33 @@ def test_calls_can_be_captured_in_a_graph(pf):
         assert torch.equal(O2, O_e)
 
 
+def test_calls_on_two_streams_with_their_own_workspaces(pf):
+    """Calls that share nothing (own inputs, outputs, workspace) may be in flight together on
+    different streams; each gives what it gives alone."""
+    import torch
+    cases = []
+    for seed, name, kw in ((1, "cfg2", dict(B=1, H=8, L=1024)), (2, "cfg3a", dict(B=1, H=4, L=512))):
+        w = synth.WORKLOADS[name].with_(seed=seed, **kw)
+        dev = to_device(w, synth.make_inputs(w))
+        need = pf.pf_delta_fwd_workspace_bytes(w.B, w.H, w.L, w.d_k, w.d_v, w.r, w.chunk, pf.PF_BF16)
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+        O_ref, S_ref = pf.delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], chunk=w.chunk, workspace=ws)
+        cases.append((w, dev, ws, need, O_ref, S_ref, torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    outs = []
+    for rep in range(4):
+        for w, dev, ws, need, O_ref, S_ref, stream in cases:
+            O = torch.empty_like(O_ref)
+            S = torch.empty_like(S_ref)
+            st = pf.pf_delta_fwd(dev["Q"], dev["K"], dev["V"], dev["beta"], dev["S0"], O, S, w.B, w.H, w.L, w.d_k, w.d_v,
+                                 w.r, w.chunk, pf.PF_BF16, ws, need, stream)
+            assert st == pf.PF_OK
+            outs.append((O, S, O_ref, S_ref))
+    torch.cuda.synchronize()
+    for O, S, O_ref, S_ref in outs:
+        assert torch.equal(O, O_ref) and torch.equal(S, S_ref)
+
+
 @pytest.mark.parametrize("name,kw", [
     ("cfg2", dict(B=1, H=2, L=4096)),                 # 16 chains -> 16 segments per head
     ("cfg1", dict(B=1, H=1, L=2048, s0_std=0.2)),     # d = 64, one head, nonzero S0
